@@ -1,0 +1,321 @@
+"""Pins for the CPU oracle: each check ties it to something other than itself
+(hand-computed values, brute force from the definition, textbook softmax,
+invariants the paper states), so that a dropped term, a wrong sign or index or
+a transposed operand fails at least one of them.  No GPU needed."""
+import os
+
+import numpy as np
+import pytest
+import scipy.special
+
+from oracle import brute, cref
+from paper_2601_04342_amd import synth
+
+GOLD = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def rand_case(B, H, T, HW, d, hidden, dprime, seed=0, std=0.3):
+    rng = np.random.default_rng(seed)
+    N = T * HW
+    q, k, v = (rng.standard_normal((B, H, N, d)) for _ in range(3))
+    shapes = dict(w1=(H, hidden, d), b1=(H, hidden), w2=(H, dprime, hidden), b2=(H, dprime))
+    phi = {n: rng.standard_normal(shapes[n[:2]]) * std for n in synth.PHI_NAMES}
+    return q, k, v, phi
+
+
+def softmax_attention(q, k, v):
+    """Eq. 2, textbook: softmax(q k^T / sqrt(d)) v, via scipy."""
+    d = q.shape[-1]
+    return scipy.special.softmax(q @ np.swapaxes(k, -1, -2) / np.sqrt(d), axis=-1) @ v
+
+
+# --- integer bookkeeping ------------------------------------------------------
+
+def test_chunk_plan_matches_hand_written_tables(plan_cases):
+    assert len(plan_cases) >= 7
+    for (T, HW, chunk, overlap), rows in plan_cases:
+        got = cref.chunk_plan(T, HW, chunk, overlap)
+        assert got.dtype == np.int64
+        assert got.tolist() == rows, (T, HW, chunk, overlap)
+
+
+@pytest.mark.parametrize("T,HW,chunk,overlap", [(21, 1560, 1, 0), (41, 1560, 1, 0),
+                                                (21, 3600, 1, 0), (21, 1560, 3, 2),
+                                                (9, 3, 4, 1)])
+def test_chunk_plan_partition_properties(T, HW, chunk, overlap):
+    p = cref.chunk_plan(T, HW, chunk, overlap)
+    N = T * HW
+    assert len(p) == -(-T // chunk)
+    assert p[0, 0] == 0 and p[-1, 1] == N
+    assert (p[1:, 0] == p[:-1, 1]).all()                  # chunks tile the tokens
+    assert ((p[:, 1] - p[:, 0])[:-1] == chunk * HW).all()  # all but the last are full
+    assert (p[:, 0] % HW == 0).all() and (p[:, 2] % HW == 0).all()
+    assert (p[:, 3] == p[:, 1]).all() and (p[:, 4] == p[:, 2]).all()
+    assert (p[:, 2] == np.maximum(p[:, 0] - overlap * HW, 0)).all()
+
+
+def test_brute_token_sets_agree_with_plan(plan_cases):
+    for (T, HW, chunk, overlap), rows in plan_cases:
+        if T * HW > 300:
+            continue
+        for q_lo, q_hi, s_lo, s_hi, l_hi in rows:
+            for i in (q_lo, q_hi - 1):
+                js, jl = brute.token_sets(i, T, HW, chunk, overlap, causal=True)
+                assert js.tolist() == list(range(s_lo, s_hi))
+                assert jl.tolist() == list(range(0, l_hi))
+                js2, jl2 = brute.token_sets(i, T, HW, chunk, overlap, causal=False)
+                assert sorted(js2.tolist() + jl2.tolist()) == list(range(T * HW))
+
+
+# --- phi ------------------------------------------------------------------------
+
+def test_phi_hand_example():
+    # values from tests/golden/tiny_closed_form.txt
+    w1, b1 = np.array([[1.0], [2.0]]), np.array([0.0, -1.0])
+    w2, b2 = np.array([[1.0, 1.0], [0.0, 2.0]]), np.array([0.0, 1.0])
+    x = np.array([[1.0], [2.0], [-3.0]])
+    want = np.array([[2.0, 9.0], [5.0, 49.0], [0.0, 1.0]])  # x=-3: u=0, psi=[0,1]
+    np.testing.assert_allclose(cref.phi(x, w1, b1, w2, b2), want, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(brute.phi_map(x, w1, b1, w2, b2), want, rtol=0, atol=1e-15)
+
+
+def test_phi_non_square_shapes_and_nonnegativity():
+    rng = np.random.default_rng(3)
+    d, h, Dp = 5, 7, 6
+    x = rng.standard_normal((11, d))
+    w1, b1 = rng.standard_normal((h, d)), rng.standard_normal(h)
+    w2, b2 = rng.standard_normal((Dp, h)), rng.standard_normal(Dp)
+    a = cref.phi(x, w1, b1, w2, b2)
+    b = brute.phi_map(x, w1, b1, w2, b2)
+    np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-13)
+    assert (a >= 0).all() and (a > 0).any()
+    # degree 3: third part is cubed
+    c = cref.phi(x, w1, b1, w2, b2, degree=3)
+    psi = np.maximum(np.maximum(x @ w1.T + b1, 0) @ w2.T + b2, 0)
+    np.testing.assert_allclose(c[:, 4:], psi[:, 4:] ** 3, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(c[:, 2:4], psi[:, 2:4] ** 2, rtol=1e-13, atol=1e-13)
+    np.testing.assert_allclose(c[:, :2], psi[:, :2], rtol=1e-13, atol=1e-13)
+
+
+def test_phi_parameter_count_matches_paper():
+    # section 4.3: about 2.4 M added parameters per converted block
+    n = synth.phi_param_count(H=12, d=128)
+    assert n == 2_371_584
+    assert abs(n - 2.4e6) / 2.4e6 < 0.02
+
+
+# --- the operator -----------------------------------------------------------------
+
+def test_closed_form_two_token_example():
+    """Eq. 5-9 by pencil and paper (tests/golden/tiny_closed_form.txt)."""
+    rows = [l.split() for l in open(os.path.join(GOLD, "tiny_closed_form.txt"))
+            if l.strip() and not l.startswith("#")]
+    gold = np.array(rows, dtype=np.float64)
+    q = np.array([1.0, 2.0]).reshape(1, 1, 2, 1)
+    k = np.array([2.0, 1.0]).reshape(1, 1, 2, 1)
+    v = np.array([3.0, -1.0]).reshape(1, 1, 2, 1)
+    w1, b1 = np.array([[[1.0], [2.0]]]), np.array([[0.0, -1.0]])
+    w2, b2 = np.array([[[1.0, 1.0], [0.0, 2.0]]]), np.array([[0.0, 1.0]])
+    phi = dict(w1_q=w1, b1_q=b1, w2_q=w2, b2_q=b2, w1_k=w1, b1_k=b1, w2_k=w2, b2_k=b2)
+    for impl in ("c", "brute"):
+        if impl == "c":
+            r = cref.forward(q, k, v, phi, T=2, HW=1, chunk=1)
+            got = dict(out=r.out, m=r.m, nS=r.nS, aS=r.aS, nL=r.nL, aL=r.aL)
+        else:
+            got = brute.forward(q, k, v, phi, T=2, HW=1, chunk=1)
+        for tok in (0, 1):
+            _, m, nS, aS, nL, aL, num, den = gold[tok]
+            assert got["m"][0, 0, tok] == pytest.approx(m, abs=1e-14)
+            assert got["nS"][0, 0, tok] == pytest.approx(nS, abs=1e-14)
+            assert got["aS"][0, 0, tok, 0] == pytest.approx(aS, abs=1e-14)
+            assert got["nL"][0, 0, tok] == pytest.approx(nL, abs=1e-11)
+            assert got["aL"][0, 0, tok, 0] == pytest.approx(aL, abs=1e-11)
+            assert got["out"][0, 0, tok, 0] == pytest.approx(num / den, rel=1e-14)
+    # stabiliser off: softmax weight of token 1 is e^2 instead of 1
+    r = cref.forward(q, k, v, phi, T=2, HW=1, chunk=1, stab=1)
+    e2 = np.exp(2.0)
+    assert r.out[0, 0, 1, 0] == pytest.approx((-e2 + 7278) / (e2 + 2426), rel=1e-14)
+    assert r.out[0, 0, 0, 0] == pytest.approx(3.0, rel=1e-14)
+
+
+CASES = [  # B, H, T, HW, d, hidden, dprime, chunk, overlap
+    (1, 2, 4, 6, 8, 12, 10, 1, 0),
+    (2, 1, 5, 3, 4, 6, 8, 2, 0),      # T % chunk != 0
+    (1, 2, 5, 4, 6, 8, 8, 2, 1),
+    (1, 1, 7, 3, 5, 6, 4, 3, 2),
+    (1, 1, 4, 5, 4, 4, 6, 1, 3),      # overlap reaches past the start
+    (1, 1, 3, 4, 4, 4, 4, 5, 0),      # one chunk covers all
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("stab", [0, 1])
+def test_recurrent_form_equals_brute_force(case, causal, stab):
+    """Section 3.3 point (2): the chunk-wise RNN and the parallel (defining)
+    form give the same output; this fixes the reading of Eq. 17-18."""
+    B, H, T, HW, d, hidden, dprime, chunk, overlap = case
+    q, k, v, phi = rand_case(B, H, T, HW, d, hidden, dprime, seed=sum(case))
+    want = brute.forward(q, k, v, phi, T, HW, chunk, overlap, causal, stab)
+    got = cref.forward(q, k, v, phi, T, HW, chunk, overlap, causal, stab)
+    for name in ("out", "m", "nS", "aS", "nL", "aL"):
+        np.testing.assert_allclose(getattr(got, name), want[name], rtol=1e-11, atol=1e-12,
+                                   err_msg=name)
+
+
+def test_tiny_baseline_config_recurrent_equals_brute():
+    """BASELINE config 1 (B=1, H=2, d=64, T=4, 8x8 tokens, chunk 1)."""
+    w = synth.WORKLOADS["tiny"]
+    q, k, v, phi = synth.make_workload(w)
+    q, k, v = (x.double().numpy() for x in (q, k, v))
+    phi = {n: p.double().numpy() for n, p in phi.items()}
+    want = brute.forward(q, k, v, phi, w.T, w.HW, w.chunk)
+    got = cref.forward(q, k, v, phi, w.T, w.HW, w.chunk)
+    np.testing.assert_allclose(got.out, want["out"], rtol=1e-11, atol=1e-13)
+    np.testing.assert_allclose(got.nL, want["nL"], rtol=1e-11, atol=1e-13)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_single_chunk_is_textbook_softmax(causal):
+    """chunk >= T: the linear set is empty, c cancels, Eq. 5 reduces to Eq. 2."""
+    q, k, v, phi = rand_case(2, 2, 3, 5, 8, 8, 8, seed=5)
+    want = softmax_attention(q, k, v)
+    for chunk in (3, 4, 100):
+        for stab in (0, 1):
+            got = cref.forward(q, k, v, phi, T=3, HW=5, chunk=chunk, causal=causal, stab=stab)
+            np.testing.assert_allclose(got.out, want, rtol=1e-12, atol=1e-13)
+            assert (got.nL == 0).all() and (got.aL == 0).all()
+
+
+def test_first_chunk_rows_are_chunk_local_softmax():
+    """s_0 = z_0 = 0 (Eq. 14-15): chunk 0 sees only its own softmax window."""
+    q, k, v, phi = rand_case(1, 2, 4, 6, 8, 8, 8, seed=7)
+    got = cref.forward(q, k, v, phi, T=4, HW=6, chunk=2)
+    want = softmax_attention(q[:, :, :12], k[:, :, :12], v[:, :, :12])
+    np.testing.assert_allclose(got.out[:, :, :12], want, rtol=1e-12, atol=1e-13)
+
+
+def test_zero_phi_gives_block_diagonal_softmax():
+    q, k, v, phi = rand_case(1, 2, 5, 4, 8, 8, 8, seed=9)
+    phi = {n: np.zeros_like(p) for n, p in phi.items()}
+    got = cref.forward(q, k, v, phi, T=5, HW=4, chunk=2)
+    for lo, hi in ((0, 8), (8, 16), (16, 20)):
+        want = softmax_attention(q[:, :, lo:hi], k[:, :, lo:hi], v[:, :, lo:hi])
+        np.testing.assert_allclose(got.out[:, :, lo:hi], want, rtol=1e-12, atol=1e-13)
+
+
+def test_overlap_window_with_zero_phi_is_windowed_softmax():
+    """Eq. 12: with phi = 0 chunk t is plain softmax over its T_c + T_o frames."""
+    q, k, v, phi = rand_case(1, 1, 6, 3, 4, 4, 4, seed=11)
+    phi = {n: np.zeros_like(p) for n, p in phi.items()}
+    got = cref.forward(q, k, v, phi, T=6, HW=3, chunk=2, overlap=1)
+    for (qlo, qhi, slo) in ((0, 6, 0), (6, 12, 3), (12, 18, 9)):
+        want = softmax_attention(q[:, :, qlo:qhi], k[:, :, slo:qhi], v[:, :, slo:qhi])
+        np.testing.assert_allclose(got.out[:, :, qlo:qhi], want, rtol=1e-12, atol=1e-13)
+
+
+def test_pure_linear_attention_limit():
+    """With the softmax weights driven to zero relative to the linear part the
+    output tends to kernelised linear attention over the earlier tokens
+    (Eq. 4): scale phi_q up so n^L >> n^S."""
+    q, k, v, phi = rand_case(1, 1, 3, 4, 4, 6, 6, seed=13)
+    phi["b2_q"] = np.abs(phi["b2_q"]) + 1.0
+    phi["b2_k"] = np.abs(phi["b2_k"]) + 1.0
+    big = dict(phi)
+    big["w2_q"] = phi["w2_q"] * 1e9
+    big["b2_q"] = phi["b2_q"] * 1e9
+    got = cref.forward(q, k, v, big, T=3, HW=4, chunk=1)
+    fq = brute.phi_map(q[0, 0], big["w1_q"][0], big["b1_q"][0], big["w2_q"][0], big["b2_q"][0])
+    fk = brute.phi_map(k[0, 0], phi["w1_k"][0], phi["b1_k"][0], phi["w2_k"][0], phi["b2_k"][0])
+    for i in range(4, 12):
+        lo = (i // 4) * 4
+        sim = fk[:lo] @ fq[i]
+        want = (sim @ v[0, 0, :lo]) / sim.sum()
+        np.testing.assert_allclose(got.out[0, 0, i], want, rtol=1e-6, atol=1e-7)
+
+
+def test_normaliser_invariants_and_convexity():
+    """phi >= 0 (section 3.1) => n^L >= 0; the row-max stabiliser makes the
+    largest softmax weight 1 => n^S >= 1; the output is a convex combination of
+    the value vectors it attends to."""
+    w = synth.WORKLOADS["tiny"]
+    q, k, v, phi = synth.make_workload(w, gain=8.0)
+    q, k, v = (x.double().numpy() for x in (q, k, v))
+    phi = {n: p.double().numpy() for n, p in phi.items()}
+    r = cref.forward(q, k, v, phi, w.T, w.HW, w.chunk)
+    assert (r.nS >= 1.0).all() and (r.nS <= w.HW).all()
+    assert (r.nL >= 0).all() and (r.nL[:, :, w.HW:] > 0).all()
+    assert (r.nL[:, :, :w.HW] == 0).all()
+    for t in range(w.T):
+        lo, hi = t * w.HW, (t + 1) * w.HW
+        vmax = v[:, :, :hi].max(axis=2, keepdims=True)
+        vmin = v[:, :, :hi].min(axis=2, keepdims=True)
+        assert (r.out[:, :, lo:hi] <= vmax + 1e-12).all()
+        assert (r.out[:, :, lo:hi] >= vmin - 1e-12).all()
+
+
+def test_constant_value_and_linearity_in_v():
+    q, k, v, phi = rand_case(1, 2, 4, 5, 6, 8, 8, seed=17)
+    const = np.broadcast_to(np.arange(6.0) - 2.5, v.shape).copy()
+    r = cref.forward(q, k, const, phi, T=4, HW=5, chunk=1, overlap=1)
+    np.testing.assert_allclose(r.out, const, rtol=1e-12, atol=1e-12)
+    v2 = np.random.default_rng(1).standard_normal(v.shape)
+    a = cref.forward(q, k, v, phi, T=4, HW=5, chunk=1).out
+    b = cref.forward(q, k, v2, phi, T=4, HW=5, chunk=1).out
+    c = cref.forward(q, k, 2.0 * v - 3.0 * v2, phi, T=4, HW=5, chunk=1).out
+    np.testing.assert_allclose(c, 2.0 * a - 3.0 * b, rtol=1e-10, atol=1e-11)
+
+
+def test_causal_prefix_consistency():
+    """Appending frames leaves earlier outputs untouched (Eq. 13); not so in the
+    bidirectional form."""
+    q, k, v, phi = rand_case(1, 1, 6, 4, 6, 8, 8, seed=19)
+    full = cref.forward(q, k, v, phi, T=6, HW=4, chunk=2, overlap=1)
+    part = cref.forward(q[:, :, :16], k[:, :, :16], v[:, :, :16], phi, T=4, HW=4, chunk=2, overlap=1)
+    np.testing.assert_array_equal(full.out[:, :, :16], part.out)
+    full_nc = cref.forward(q, k, v, phi, T=6, HW=4, chunk=2, overlap=1, causal=False)
+    assert np.abs(full_nc.out[:, :, :16] - part.out).max() > 1e-6
+
+
+def test_permutation_invariance_within_sets():
+    q, k, v, phi = rand_case(1, 1, 3, 6, 6, 8, 8, seed=23)
+    base = cref.forward(q, k, v, phi, T=3, HW=6, chunk=1).out
+    perm = np.arange(18)
+    rng = np.random.default_rng(0)
+    perm[:6] = rng.permutation(6)            # inside chunk 0 (a linear set for t >= 1)
+    perm[12:] = 12 + rng.permutation(6)      # inside chunk 2's softmax window
+    out = cref.forward(q, k[:, :, perm], v[:, :, perm], phi, T=3, HW=6, chunk=1).out
+    # rows of chunk 1 see chunk 0 only through the linear set: unchanged
+    np.testing.assert_allclose(out[:, :, 6:12], base[:, :, 6:12], rtol=1e-12, atol=1e-13)
+    # rows of chunk 2: window permuted (k, v together): unchanged
+    np.testing.assert_allclose(out[:, :, 12:], base[:, :, 12:], rtol=1e-12, atol=1e-13)
+
+
+def test_row_subset_matches_full_evaluation():
+    q, k, v, phi = rand_case(2, 2, 5, 4, 6, 8, 8, seed=29)
+    full = cref.forward(q, k, v, phi, T=5, HW=4, chunk=2, overlap=1)
+    rows = np.array([0, 3, 8, 9, 17, 19])
+    sub = cref.forward(q, k, v, phi, T=5, HW=4, chunk=2, overlap=1, rows=rows)
+    for name in ("out", "m", "nS", "aS", "nL", "aL"):
+        np.testing.assert_array_equal(getattr(sub, name), getattr(full, name)[:, :, rows])
+
+
+def test_state_matches_definition():
+    """S = sum phi_k(k_j) v_j^T, z = sum phi_k(k_j) (Eq. 4 / Eq. 17-18)."""
+    q, k, v, phi = rand_case(1, 1, 3, 5, 6, 8, 10, seed=31)
+    S, z = cref.state(k[0, 0], v[0, 0], 11, phi["w1_k"][0], phi["b1_k"][0], phi["w2_k"][0],
+                      phi["b2_k"][0])
+    fk = brute.phi_map(k[0, 0, :11], phi["w1_k"][0], phi["b1_k"][0], phi["w2_k"][0],
+                       phi["b2_k"][0])
+    np.testing.assert_allclose(S, fk.T @ v[0, 0, :11], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(z, fk.sum(axis=0), rtol=1e-12, atol=1e-13)
+
+
+def test_bad_arguments_are_rejected():
+    q, k, v, phi = rand_case(1, 1, 2, 2, 4, 4, 4, seed=1)
+    with pytest.raises(ValueError):
+        cref.chunk_plan(0, 4, 1, 0)
+    with pytest.raises(ValueError):
+        cref.forward(q, k, v, phi, T=2, HW=2, chunk=1, rows=np.array([3, 1]))
+    with pytest.raises(ValueError):
+        cref.forward(q, k, v, phi, T=2, HW=2, chunk=1, degree=3)
