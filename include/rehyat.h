@@ -1,0 +1,169 @@
+/*
+ * rehyat.h -- C ABI of the MI355X (gfx950) Recurrent Hybrid Attention library.
+ *
+ * The operator is the hybrid attention of the ReHyAt paper, section 3.2
+ * (Eq. 5-9: softmax attention inside a temporal chunk and kernelised linear
+ * attention through learned feature maps phi_q, phi_k outside it, under one
+ * joint normaliser), in its causal chunk-recurrent form of section 3.3
+ * (Eq. 13-18: the linear part is read from a running state S = sum phi_k(k) v^T,
+ * z = sum phi_k(k) over the tokens that have left the softmax window).
+ *
+ * Conventions shared by every entry point
+ *  - Return value: REHYAT_OK (0) or a negative REHYAT_E_* code.  On a
+ *    validation error nothing is launched and `out` is not written.  No
+ *    exception or abort crosses this boundary.
+ *  - q, k, v, out, the phi tensors and the workspace are DEVICE pointers owned
+ *    by the caller; the library never frees or retains them beyond the call
+ *    (the workspace pointer given to rehyat_set_workspace is retained until it
+ *    is replaced or rehyat_shutdown is called).
+ *  - Work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ *    default stream) and the call returns without synchronising.
+ *  - Tensors are contiguous, row-major, bf16 (IEEE bfloat16 bit patterns)
+ *    unless stated otherwise.  Token index inside a head is
+ *    frame * HW + position, frame-major, as in section 3.2's flattening of the
+ *    (T, H, W) latent.
+ *  - Results are deterministic: repeated calls give bit-identical outputs.
+ *  - Calls that share a workspace must be ordered on one stream.
+ */
+#ifndef REHYAT_H_
+#define REHYAT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define REHYAT_OK 0
+#define REHYAT_E_NULL (-1)        /* a required pointer is NULL */
+#define REHYAT_E_SHAPE (-2)       /* a size is non-positive or inconsistent */
+#define REHYAT_E_UNSUPPORTED (-3) /* valid in the paper, not built here */
+#define REHYAT_E_WORKSPACE (-4)   /* workspace missing, too small or misaligned */
+#define REHYAT_E_HIP (-5)         /* a HIP runtime call failed */
+
+/* Stabiliser c of Eq. 6 and Eq. 8.  The linear terms of Eq. 7 and 9 are not
+ * rescaled by exp(-c), so the choice is part of the operator's definition. */
+#define REHYAT_STAB_ROWMAX 0 /* c = largest exponent of the query row */
+#define REHYAT_STAB_NONE 1   /* c = 0 (evaluated without overflow) */
+
+/*
+ * Feature maps phi_q and phi_k (section 3.2, "Characterization of phi";
+ * appendix "Training Details": a two-layer per-head MLP followed by a split
+ * into `degree` equal parts, part p raised element-wise to the power p):
+ *   u = relu(W1 x + b1),  psi = relu(W2 u + b2),
+ *   phi(x) = [psi[0 : D'/2], psi[D'/2 : D']^2]          (degree 2)
+ * The struct lives in HOST memory; its pointer fields are DEVICE pointers:
+ *   w1_* [H, hidden, d] bf16     b1_* [H, hidden] fp32
+ *   w2_* [H, dprime, hidden] bf16  b2_* [H, dprime] fp32
+ * Supported here: hidden == dprime == 2*d, degree == 2, act == 0 (ReLU).
+ */
+typedef struct {
+  const void *w1_q, *b1_q, *w2_q, *b2_q;
+  const void *w1_k, *b1_k, *w2_k, *b2_k;
+  int32_t hidden;
+  int32_t dprime;
+  int32_t degree;
+  int32_t act;
+} rehyat_phi_params;
+
+/*
+ * Optional per-row components of Eq. 5-9 (test hook).  HOST struct of DEVICE
+ * pointers, each nullable, all fp32:
+ *   m  [B,H,N]    largest softmax exponent q_i.k_j/sqrt(d) of the row
+ *   nS [B,H,N]    Eq. 8      aS [B,H,N,d]  Eq. 6   (both relative to exp(-m))
+ *   nL [B,H,N]    Eq. 9      aL [B,H,N,d]  Eq. 7
+ * With REHYAT_STAB_NONE, nL and aL are reported multiplied by exp(-m), the
+ * scale on which they are merged with nS and aS.
+ */
+typedef struct {
+  float *m, *nS, *aS, *nL, *aL;
+} rehyat_debug_out;
+
+/*
+ * Chunk bookkeeping on the host (section 3.2 token layout; Eq. 12; Eq. 13).
+ * Writes n_chunks = ceil(T / chunk) rows of five int64 to `table` (HOST
+ * memory, may be NULL to query the count only):
+ *   q_lo, q_hi : query token range of the chunk
+ *   s_lo, s_hi : softmax window [max(q_lo - overlap*HW, 0), q_hi)
+ *   l_hi       : the causal linear set is [0, l_hi), l_hi == s_lo
+ * The kernels derive their ranges from the same formulas.
+ * Errors: REHYAT_E_NULL (n_chunks NULL), REHYAT_E_SHAPE.
+ */
+int rehyat_chunk_plan(int T, int HW, int chunk, int overlap, int64_t *table,
+                      int *n_chunks);
+
+/*
+ * Bytes of device workspace a forward call needs: chunk-state partial sums,
+ * their prefix (the states S_t, z_t of Eq. 16) and the carry between windows
+ * of chunks.  Depends on B, H, d and dprime only -- not on T, HW or chunk --
+ * which is the constant-memory property of section 3.3, point (3).
+ * Returns 0 for unsupported sizes.
+ */
+size_t rehyat_workspace_bytes(int B, int H, int d, int dprime);
+
+/*
+ * Give the library a caller-owned DEVICE workspace (256-byte aligned).  If no
+ * workspace has been set, or the one set is too small for a call, the library
+ * allocates its own with hipMalloc on first need and keeps it until
+ * rehyat_shutdown().  Pass (NULL, 0) to return to library-owned memory.
+ */
+int rehyat_set_workspace(void *dev_ptr, size_t bytes);
+
+/*
+ * Hybrid attention forward (Eq. 5-9 with the causal sets of Eq. 13, evaluated
+ * chunk-wise as Eq. 14-18), T_o = 0, row-max stabiliser.
+ *   q, k, v : [B, H, N, d] bf16, N = T*HW        out : [B, H, N, d] bf16
+ *   phi_params : HOST pointer (see above)
+ *   T   latent frames, HW tokens per frame, chunk = T_c frames per chunk
+ *       (a short last chunk when T % chunk != 0; chunk >= T is one chunk,
+ *       i.e. plain softmax attention, Eq. 2)
+ * Supported: d in {64, 128}; B*H*N*d < 2^62; N < 2^31.
+ */
+int rehyat_forward(const void *q, const void *k, const void *v,
+                   const rehyat_phi_params *phi_params, void *out, int B, int H,
+                   int T, int HW, int d, int chunk, void *stream);
+
+/*
+ * Same operator with the remaining knobs of the paper:
+ *   overlap   : T_o latent frames by which the softmax window reaches back
+ *               (Eq. 12); the state then lags by the same amount (Eq. 13)
+ *   causal    : 1 = Eq. 13 (built).  0 = the bidirectional sets of Eq. 11-12:
+ *               REHYAT_E_UNSUPPORTED in this build
+ *   stab_mode : REHYAT_STAB_ROWMAX or REHYAT_STAB_NONE
+ *   debug     : NULL, or HOST pointer to the component outputs
+ */
+int rehyat_forward_ex(const void *q, const void *k, const void *v,
+                      const rehyat_phi_params *phi_params, void *out, int B,
+                      int H, int T, int HW, int d, int chunk, int overlap,
+                      int causal, int stab_mode, const rehyat_debug_out *debug,
+                      void *stream);
+
+/*
+ * Running state of the chunk-wise RNN (Eq. 14-15, 17-18) after absorbing
+ * tokens [0, upto) of every head, as the state kernels compute it:
+ *   S_out [B, H, dprime, d] fp32,  z_out [B, H, dprime] fp32  (DEVICE)
+ * `upto` must be a multiple of HW.  Test hook for the state and prefix
+ * kernels; uses the workspace like a forward call.
+ */
+int rehyat_state(const void *k, const void *v,
+                 const rehyat_phi_params *phi_params, float *S_out, float *z_out,
+                 int B, int H, int T, int HW, int d, int upto_frames,
+                 void *stream);
+
+/* Free library-owned device memory.  Safe to call more than once. */
+int rehyat_shutdown(void);
+
+/* Static string for a status code. */
+const char *rehyat_status_string(int code);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int rehyat_version(void);
+
+/* Text of the last HIP error seen by this library ("" if none). */
+const char *rehyat_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REHYAT_H_ */

@@ -1,0 +1,368 @@
+// Host side of the C ABI declared in include/rehyat.h: argument validation, the
+// window plan over chunks, workspace carving and kernel launches.  No numerics
+// happen here.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+#include "../../include/rehyat.h"
+#include "rehyat_kernels.h"
+
+namespace {
+
+using namespace rehyat;
+
+constexpr int kPartialSlots = 64;  // (segment, piece) partial sums per (b, h) in flight
+constexpr int kStateSlots = 32;    // chunk states per (b, h) in flight = window length
+constexpr int kMaxSplit = 8;
+constexpr int kCUs = 256;
+
+struct Workspace {
+  void* ptr = nullptr;
+  size_t bytes = 0;
+  bool owned = false;
+};
+Workspace g_ws;
+std::mutex g_mu;
+char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e, const char* what) {
+  snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
+  return REHYAT_E_HIP;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct WsLayout {
+  size_t partial, state_s, state_z, carry, total;
+};
+
+WsLayout ws_layout(int B, int H, int d, int dp) {
+  const size_t BH = (size_t)B * H;
+  const size_t elems = (size_t)d * dp + dp;
+  WsLayout L;
+  size_t off = 0;
+  L.partial = off;
+  off += align256(BH * kPartialSlots * elems * sizeof(float));
+  L.state_s = off;
+  off += align256(BH * kStateSlots * (size_t)d * dp * sizeof(bf16_t));
+  L.state_z = off;
+  off += align256(BH * kStateSlots * (size_t)dp * sizeof(float));
+  L.carry = off;
+  off += align256(BH * elems * sizeof(float));
+  L.total = off;
+  return L;
+}
+
+bool supported_dims(int d, int dp) { return (d == 64 || d == 128) && dp == 2 * d; }
+
+int ensure_workspace(size_t need, char** base) {
+  if (g_ws.ptr && g_ws.bytes >= need) {
+    *base = (char*)g_ws.ptr;
+    return REHYAT_OK;
+  }
+  if (g_ws.ptr && !g_ws.owned) {
+    // a caller-owned workspace that is too small is replaced by a library-owned one
+    g_ws = Workspace();
+  }
+  if (g_ws.ptr && g_ws.owned) {
+    hipError_t e = hipFree(g_ws.ptr);
+    g_ws = Workspace();
+    if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
+  }
+  void* p = nullptr;
+  hipError_t e = hipMalloc(&p, need);
+  if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
+  g_ws.ptr = p;
+  g_ws.bytes = need;
+  g_ws.owned = true;
+  *base = (char*)p;
+  return REHYAT_OK;
+}
+
+int check_phi(const rehyat_phi_params* p, int d) {
+  if (!p) return REHYAT_E_NULL;
+  if (!p->w1_q || !p->b1_q || !p->w2_q || !p->b2_q || !p->w1_k || !p->b1_k || !p->w2_k || !p->b2_k)
+    return REHYAT_E_NULL;
+  if (p->hidden < 1 || p->dprime < 1 || p->degree < 1) return REHYAT_E_SHAPE;
+  if (p->dprime % p->degree) return REHYAT_E_SHAPE;
+  if (p->hidden != 2 * d || p->dprime != 2 * d || p->degree != 2 || p->act != 0)
+    return REHYAT_E_UNSUPPORTED;
+  return REHYAT_OK;
+}
+
+// pieces per segment: more workgroups when (b, h, segment) alone cannot fill the chip
+int choose_nsplit(int BH, int n_seg_total) {
+  if (n_seg_total < 1) return 1;
+  int best = 1;
+  double best_cost = 1e30;
+  for (int ns = 1; ns <= kMaxSplit; ++ns) {
+    int win = kPartialSlots / ns;
+    if (win > kStateSlots) win = kStateSlots;
+    const int segs = n_seg_total < win ? n_seg_total : win;
+    const int windows = (n_seg_total + win - 1) / win;
+    const long wgs = (long)BH * segs * ns;
+    const double rounds = std::ceil((double)wgs / kCUs);
+    // time in units of "one whole segment on one CU"
+    const double cost = windows * rounds / ns;
+    if (cost < best_cost * 0.9) {
+      best_cost = cost;
+      best = ns;
+    }
+  }
+  return best;
+}
+
+int launch_state_window(const void* k, const void* v, const rehyat_phi_params* phi, char* ws,
+                        const WsLayout& L, int B, int H, int T, int HW, int d, int chunk, int overlap,
+                        int chunk0, int n_seg, int nsplit, hipStream_t stream) {
+  StateArgs s;
+  s.k = (const bf16_t*)k;
+  s.v = (const bf16_t*)v;
+  s.w1_k = (const bf16_t*)phi->w1_k;
+  s.b1_k = (const float*)phi->b1_k;
+  s.w2_k = (const bf16_t*)phi->w2_k;
+  s.b2_k = (const float*)phi->b2_k;
+  s.partial = (float*)(ws + L.partial);
+  s.H = H;
+  s.T = T;
+  s.HW = HW;
+  s.chunk = chunk;
+  s.overlap = overlap;
+  s.chunk0 = chunk0;
+  s.n_seg = n_seg;
+  s.nsplit = nsplit;
+  s.partial_slots = kPartialSlots;
+  s.n_items = B * H * n_seg * nsplit;
+  s.items_per_xcd = (s.n_items + 7) / 8;
+  hipError_t e = launch_state(s, d, s.items_per_xcd * 8, stream);
+  if (e != hipSuccess) return hip_fail(e, "state kernel launch");
+  return REHYAT_OK;
+}
+
+int launch_prefix_window(char* ws, const WsLayout& L, int B, int H, int d, int dp, int n_chunks,
+                         int n_seg, int nsplit, bool first, hipStream_t stream) {
+  PrefixArgs p;
+  p.partial = (const float*)(ws + L.partial);
+  p.carry = (float*)(ws + L.carry);
+  p.state_s = (bf16_t*)(ws + L.state_s);
+  p.state_z = (float*)(ws + L.state_z);
+  p.BH = B * H;
+  p.n_chunks = n_chunks;
+  p.n_seg = n_seg;
+  p.nsplit = nsplit;
+  p.partial_slots = kPartialSlots;
+  p.state_slots = kStateSlots;
+  p.first_window = first ? 1 : 0;
+  p.elems = d * dp + dp;
+  p.s_elems = d * dp;
+  hipError_t e = launch_prefix(p, stream);
+  if (e != hipSuccess) return hip_fail(e, "prefix kernel launch");
+  return REHYAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rehyat_version(void) { return 100; }
+
+const char* rehyat_status_string(int code) {
+  switch (code) {
+    case REHYAT_OK: return "ok";
+    case REHYAT_E_NULL: return "a required pointer is NULL";
+    case REHYAT_E_SHAPE: return "a size is non-positive or inconsistent";
+    case REHYAT_E_UNSUPPORTED: return "configuration not supported by this build";
+    case REHYAT_E_WORKSPACE: return "workspace missing, too small or misaligned";
+    case REHYAT_E_HIP: return "a HIP runtime call failed";
+    default: return "unknown status code";
+  }
+}
+
+const char* rehyat_last_hip_error(void) { return g_hip_err; }
+
+int rehyat_chunk_plan(int T, int HW, int chunk, int overlap, int64_t* table, int* n_chunks) {
+  if (!n_chunks) return REHYAT_E_NULL;
+  if (T < 1 || HW < 1 || chunk < 1 || overlap < 0) return REHYAT_E_SHAPE;
+  const int nc = num_chunks(T, chunk);
+  if (table) {
+    for (int t = 0; t < nc; ++t) {
+      ChunkRange r = chunk_range(T, HW, chunk, overlap, t);
+      int64_t* row = table + 5 * (int64_t)t;
+      row[0] = r.q_lo;
+      row[1] = r.q_hi;
+      row[2] = r.s_lo;
+      row[3] = r.s_hi;
+      row[4] = r.l_hi;
+    }
+  }
+  *n_chunks = nc;
+  return REHYAT_OK;
+}
+
+size_t rehyat_workspace_bytes(int B, int H, int d, int dprime) {
+  if (B < 1 || H < 1 || !supported_dims(d, dprime)) return 0;
+  return ws_layout(B, H, d, dprime).total;
+}
+
+int rehyat_set_workspace(void* dev_ptr, size_t bytes) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (dev_ptr && (((uintptr_t)dev_ptr) & 255)) return REHYAT_E_WORKSPACE;
+  if (dev_ptr && bytes == 0) return REHYAT_E_WORKSPACE;
+  if (g_ws.ptr && g_ws.owned) {
+    hipError_t e = hipFree(g_ws.ptr);
+    g_ws = Workspace();
+    if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
+  }
+  g_ws = Workspace();
+  if (dev_ptr) {
+    g_ws.ptr = dev_ptr;
+    g_ws.bytes = bytes;
+    g_ws.owned = false;
+  }
+  return REHYAT_OK;
+}
+
+int rehyat_shutdown(void) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  if (g_ws.ptr && g_ws.owned) {
+    hipError_t e = hipFree(g_ws.ptr);
+    g_ws = Workspace();
+    if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
+  }
+  g_ws = Workspace();
+  return REHYAT_OK;
+}
+
+int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                      void* out, int B, int H, int T, int HW, int d, int chunk, int overlap,
+                      int causal, int stab_mode, const rehyat_debug_out* debug, void* stream) {
+  if (!q || !k || !v || !out) return REHYAT_E_NULL;
+  if (B < 1 || H < 1 || T < 1 || HW < 1 || d < 1 || chunk < 1 || overlap < 0) return REHYAT_E_SHAPE;
+  if ((int64_t)T * HW >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
+  if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
+  int rc = check_phi(phi, d);
+  if (rc != REHYAT_OK) return rc;
+  if (stab_mode != REHYAT_STAB_ROWMAX && stab_mode != REHYAT_STAB_NONE) return REHYAT_E_SHAPE;
+  if (causal != 0 && causal != 1) return REHYAT_E_SHAPE;
+  if (causal == 0) return REHYAT_E_UNSUPPORTED;
+  const int dp = phi->dprime;
+  hipStream_t st = (hipStream_t)stream;
+
+  std::lock_guard<std::mutex> lock(g_mu);
+  const WsLayout L = ws_layout(B, H, d, dp);
+  char* ws = nullptr;
+  rc = ensure_workspace(L.total, &ws);
+  if (rc != REHYAT_OK) return rc;
+
+  const int nc = num_chunks(T, chunk);
+  const int nsplit = choose_nsplit(B * H, nc - 1);
+  int win = kPartialSlots / nsplit;
+  if (win > kStateSlots) win = kStateSlots;
+  const int chunk_frames = chunk < T ? chunk : T;
+  const int qtiles = (int)(((int64_t)chunk_frames * HW + 255) / 256);
+
+  for (int c0 = 0; c0 < nc; c0 += win) {
+    const int c1 = (c0 + win < nc) ? c0 + win : nc;
+    const int n_chunks = c1 - c0;
+    const int n_seg = (c1 < nc) ? n_chunks : n_chunks - 1;
+    if (n_seg > 0) {
+      rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, chunk, overlap, c0, n_seg, nsplit, st);
+      if (rc != REHYAT_OK) return rc;
+    }
+    if (nc > 1) {
+      rc = launch_prefix_window(ws, L, B, H, d, dp, n_chunks, n_seg, nsplit, c0 == 0, st);
+      if (rc != REHYAT_OK) return rc;
+    }
+    AttnArgs a;
+    a.q = (const bf16_t*)q;
+    a.k = (const bf16_t*)k;
+    a.v = (const bf16_t*)v;
+    a.out = (bf16_t*)out;
+    a.w1_q = (const bf16_t*)phi->w1_q;
+    a.b1_q = (const float*)phi->b1_q;
+    a.w2_q = (const bf16_t*)phi->w2_q;
+    a.b2_q = (const float*)phi->b2_q;
+    a.state_s = (const bf16_t*)(ws + L.state_s);
+    a.state_z = (const float*)(ws + L.state_z);
+    a.dbg_m = debug ? debug->m : nullptr;
+    a.dbg_nS = debug ? debug->nS : nullptr;
+    a.dbg_aS = debug ? debug->aS : nullptr;
+    a.dbg_nL = debug ? debug->nL : nullptr;
+    a.dbg_aL = debug ? debug->aL : nullptr;
+    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)d));
+    a.H = H;
+    a.T = T;
+    a.HW = HW;
+    a.chunk = chunk;
+    a.overlap = overlap;
+    a.chunk0 = c0;
+    a.n_win_chunks = n_chunks;
+    a.qtiles = qtiles;
+    a.state_slots = kStateSlots;
+    a.stab_mode = stab_mode;
+    a.n_items = B * H * n_chunks * qtiles;
+    a.items_per_xcd = (a.n_items + 7) / 8;
+    hipError_t e = launch_attn(a, d, a.items_per_xcd * 8, st);
+    if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
+  }
+  return REHYAT_OK;
+}
+
+int rehyat_forward(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                   void* out, int B, int H, int T, int HW, int d, int chunk, void* stream) {
+  return rehyat_forward_ex(q, k, v, phi, out, B, H, T, HW, d, chunk, /*overlap=*/0, /*causal=*/1,
+                           REHYAT_STAB_ROWMAX, nullptr, stream);
+}
+
+int rehyat_state(const void* k, const void* v, const rehyat_phi_params* phi, float* S_out,
+                 float* z_out, int B, int H, int T, int HW, int d, int upto_frames, void* stream) {
+  if (!k || !v || !S_out || !z_out) return REHYAT_E_NULL;
+  if (B < 1 || H < 1 || T < 1 || HW < 1 || d < 1) return REHYAT_E_SHAPE;
+  if (upto_frames < 0 || upto_frames > T) return REHYAT_E_SHAPE;
+  if ((int64_t)T * HW >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
+  int rc = check_phi(phi, d);
+  if (rc != REHYAT_OK) return rc;
+  const int dp = phi->dprime;
+  hipStream_t st = (hipStream_t)stream;
+  const size_t BH = (size_t)B * H;
+  if (upto_frames == 0) {
+    hipError_t e = hipMemsetAsync(S_out, 0, BH * d * dp * sizeof(float), st);
+    if (e == hipSuccess) e = hipMemsetAsync(z_out, 0, BH * dp * sizeof(float), st);
+    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(state)");
+    return REHYAT_OK;
+  }
+  std::lock_guard<std::mutex> lock(g_mu);
+  const WsLayout L = ws_layout(B, H, d, dp);
+  char* ws = nullptr;
+  rc = ensure_workspace(L.total, &ws);
+  if (rc != REHYAT_OK) return rc;
+  // one frame per chunk, no overlap: segment f is frame f
+  const int nsplit = choose_nsplit(B * H, upto_frames);
+  int win = kPartialSlots / nsplit;
+  if (win > kStateSlots) win = kStateSlots;
+  for (int c0 = 0; c0 < upto_frames; c0 += win) {
+    const int n_seg = (upto_frames - c0 < win) ? upto_frames - c0 : win;
+    rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, 1, 0, c0, n_seg, nsplit, st);
+    if (rc != REHYAT_OK) return rc;
+    rc = launch_prefix_window(ws, L, B, H, d, dp, n_seg, n_seg, nsplit, c0 == 0, st);
+    if (rc != REHYAT_OK) return rc;
+  }
+  StateOutArgs o;
+  o.carry = (const float*)(ws + L.carry);
+  o.S_out = S_out;
+  o.z_out = z_out;
+  o.BH = B * H;
+  o.d = d;
+  o.dprime = dp;
+  hipError_t e = launch_state_out(o, st);
+  if (e != hipSuccess) return hip_fail(e, "state output kernel launch");
+  return REHYAT_OK;
+}
+
+}  // extern "C"

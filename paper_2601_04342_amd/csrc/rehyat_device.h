@@ -1,0 +1,186 @@
+// Device-side building blocks shared by the gfx950 kernels of the hybrid
+// attention library: vector types, the bf16 MFMA wrapper with its operand
+// layout, LDS tile staging and the chunk bookkeeping formulas.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rehyat {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(float)))) float f32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short i16x4;
+
+typedef uint16_t bf16_t;  // storage type of a bf16 value
+
+constexpr int kWave = 64;
+
+// ---------------------------------------------------------------------------
+// Chunk bookkeeping (section 3.2 token layout; Eq. 12; Eq. 13).  The host
+// entry point rehyat_chunk_plan and every kernel use this one function.
+// ---------------------------------------------------------------------------
+struct ChunkRange {
+  int64_t q_lo, q_hi;  // query tokens of the chunk
+  int64_t s_lo, s_hi;  // softmax window
+  int64_t l_hi;        // causal linear set is [0, l_hi)
+};
+
+__host__ __device__ inline int num_chunks(int T, int chunk) {
+  return (T + chunk - 1) / chunk;
+}
+
+__host__ __device__ inline ChunkRange chunk_range(int T, int HW, int chunk, int overlap, int t) {
+  ChunkRange r;
+  int64_t f0 = (int64_t)t * chunk;
+  int64_t f1 = f0 + chunk;
+  if (f1 > T) f1 = T;
+  r.q_lo = f0 * HW;
+  r.q_hi = f1 * HW;
+  int64_t s = r.q_lo - (int64_t)overlap * HW;
+  r.s_lo = s < 0 ? 0 : s;
+  r.s_hi = r.q_hi;
+  r.l_hi = r.s_lo;
+  return r;
+}
+
+// ---------------------------------------------------------------------------
+// v_mfma_f32_32x32x16_bf16: D[32x32] += A[32x16] * B[16x32].
+// Lane l = 32*g + r holds A[r][8g .. 8g+7] and B[8g .. 8g+7][r]; accumulator
+// register 4*i + j of lane l holds D[8i + 4g + j][r].
+// Because the contraction index may be permuted freely as long as A and B
+// agree, an accumulator (rows 8i+4g+j in registers) converts in place into
+// the B operand of a following product: registers 8s .. 8s+7 become the eight
+// k-values of k-step s, which are rows 16s + {4g..4g+3, 8+4g..8+4g+3}.  The
+// matching A operand is read from a tile whose 16-element groups are stored
+// with their two middle quads swapped ("quad-swapped" layout, see
+// stage_tile<true>), or through transposing LDS reads for row-major data.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+__device__ __forceinline__ float bf16_round(float x) {
+  // value of x after round-to-nearest-even to bf16
+  uint32_t u = pack_bf16(x, 0.f) << 16;
+  return __builtin_bit_cast(float, u);
+}
+
+// Registers 8s .. 8s+7 of an accumulator -> one bf16 B operand.
+__device__ __forceinline__ bf16x8 acc_to_operand(const f32x16& c, int s) {
+  u32x4 p;
+  p[0] = pack_bf16(c[8 * s + 0], c[8 * s + 1]);
+  p[1] = pack_bf16(c[8 * s + 2], c[8 * s + 3]);
+  p[2] = pack_bf16(c[8 * s + 4], c[8 * s + 5]);
+  p[3] = pack_bf16(c[8 * s + 6], c[8 * s + 7]);
+  return __builtin_bit_cast(bf16x8, p);
+}
+
+__device__ __forceinline__ bf16x8 lds_read_frag(const bf16_t* p) {
+  return *reinterpret_cast<const bf16x8*>(p);
+}
+
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes,
+// lane i passes the address of 4 consecutive bf16 of row (i / 4) at column
+// group (i % 4) of a 4 x 16 block and receives column i of that block, rows
+// 0..3.
+__device__ __forceinline__ i16x4 lds_read_tr(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) i16x4*)(p));
+}
+
+// A operand taken from a row-major [token][feature] LDS tile as its transpose:
+// rows of the operand are 32 features starting at `col0`, the eight k-values of
+// lane half g are tokens row0 + {4g..4g+3, 8+4g..8+4g+3} (the order produced by
+// acc_to_operand).  `ld` is the tile's row stride in elements.
+__device__ __forceinline__ bf16x8 lds_read_frag_transposed(const bf16_t* tile, int ld,
+                                                         int row0, int col0, int lane) {
+  const int g = lane >> 5;
+  const int r = lane & 31;
+  const int i = lane & 15;
+  const bf16_t* p = tile + (row0 + 4 * g + (i >> 2)) * ld + col0 + 16 * (r >> 4) + 4 * (i & 3);
+  i16x4 lo = lds_read_tr(p);
+  i16x4 hi = lds_read_tr(p + 8 * ld);
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short i16x8;
+  i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+// ---------------------------------------------------------------------------
+// Cooperative global -> LDS staging of a [ROWS][COLS] bf16 tile by NT threads,
+// split into a load half (global -> registers, issued early) and a store half
+// (registers -> LDS, after the previous tile's readers have passed a barrier).
+// Rows at or beyond `valid_rows` are filled with zeros.  With SWAP the two
+// middle quads of every 16-column group are exchanged on the way in.
+// ---------------------------------------------------------------------------
+template <int ROWS, int COLS, int NT>
+struct TileRegs {
+  static constexpr int VPR = COLS / 8;               // 16-byte vectors per row
+  static constexpr int NV = (ROWS * VPR + NT - 1) / NT;  // vectors per thread
+  u32x4 v[NV];
+};
+
+template <int ROWS, int COLS, int NT>
+__device__ __forceinline__ void tile_load(TileRegs<ROWS, COLS, NT>& regs, const bf16_t* src,
+                                          int64_t src_ld, int valid_rows, int tid) {
+  constexpr int VPR = COLS / 8;
+#pragma unroll
+  for (int n = 0; n < TileRegs<ROWS, COLS, NT>::NV; ++n) {
+    const int vi = tid + n * NT;
+    const int row = vi / VPR;
+    const int cv = vi % VPR;
+    u32x4 x = {0u, 0u, 0u, 0u};
+    if (row < ROWS && row < valid_rows)
+      x = *reinterpret_cast<const u32x4*>(src + (int64_t)row * src_ld + cv * 8);
+    regs.v[n] = x;
+  }
+}
+
+template <int ROWS, int COLS, int NT, bool SWAP>
+__device__ __forceinline__ void tile_store(const TileRegs<ROWS, COLS, NT>& regs, bf16_t* dst,
+                                           int dst_ld, int tid) {
+  constexpr int VPR = COLS / 8;
+#pragma unroll
+  for (int n = 0; n < TileRegs<ROWS, COLS, NT>::NV; ++n) {
+    const int vi = tid + n * NT;
+    const int row = vi / VPR;
+    const int cv = vi % VPR;
+    if (row < ROWS) {
+      bf16_t* p = dst + row * dst_ld + cv * 8;
+      if (!SWAP) {
+        *reinterpret_cast<u32x4*>(p) = regs.v[n];
+      } else {
+        // columns 16m+0..7 (cv even): quad 0 stays, quad 1 goes to position 8
+        // columns 16m+8..15 (cv odd): quad 2 goes to position 4, quad 3 stays
+        u32x2 a = {regs.v[n][0], regs.v[n][1]};
+        u32x2 b = {regs.v[n][2], regs.v[n][3]};
+        if ((cv & 1) == 0) {
+          *reinterpret_cast<u32x2*>(p) = a;
+          *reinterpret_cast<u32x2*>(p + 8) = b;
+        } else {
+          *reinterpret_cast<u32x2*>(p - 4) = a;
+          *reinterpret_cast<u32x2*>(p + 4) = b;
+        }
+      }
+    }
+  }
+}
+
+// Workgroup index -> logical work item so that consecutive logical items run
+// on the same XCD: hardware deals workgroups round-robin over the 8 XCDs, each
+// with its own L2, and items that share K/V or weights are consecutive.
+__device__ __forceinline__ int xcd_swizzle(int wg, int per_xcd) {
+  return (wg & 7) * per_xcd + (wg >> 3);
+}
+
+}  // namespace rehyat

@@ -1,0 +1,81 @@
+// Internal launch interfaces between the C-ABI host layer and the kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rehyat_device.h"
+
+namespace rehyat {
+
+// ---- chunk-state kernel: partial sums of phi_k(K)^T V and phi_k(K) ----------
+// Segment s of a window is the token range that enters the linear set between
+// chunk (chunk0 + s) and the next one, [s_lo(chunk0+s), s_lo(chunk0+s+1))
+// (Eq. 13, Eq. 17-18); each segment is cut into `nsplit` pieces, one workgroup
+// per (batch*head, segment, piece).
+struct StateArgs {
+  const bf16_t* k;      // [BH, N, d]
+  const bf16_t* v;      // [BH, N, d]
+  const bf16_t* w1_k;   // [H, hidden, d]
+  const float* b1_k;    // [H, hidden]
+  const bf16_t* w2_k;   // [H, dprime, hidden]
+  const float* b2_k;    // [H, dprime]
+  float* partial;       // [BH, partial_slots, d*dprime + dprime] (S^T [d][dprime], then z)
+  int H, T, HW, chunk, overlap;
+  int chunk0;           // first chunk of the window
+  int n_seg;            // segments computed in this launch
+  int nsplit;           // pieces per segment
+  int partial_slots;    // slot stride per (b, h)
+  int n_items;          // BH * n_seg * nsplit
+  int items_per_xcd;
+};
+
+// ---- prefix kernel: states S_t, z_t of the window's chunks ---------------------
+struct PrefixArgs {
+  const float* partial;  // as written by the state kernel
+  float* carry;          // [BH, d*dprime + dprime] fp32, state at the window's first chunk
+  bf16_t* state_s;       // [BH, state_slots, d, dprime] bf16 (S_t transposed)
+  float* state_z;        // [BH, state_slots, dprime]
+  int BH;
+  int n_chunks;          // chunks in the window (states written)
+  int n_seg;             // segments available (n_chunks or n_chunks - 1)
+  int nsplit;
+  int partial_slots, state_slots;
+  int first_window;      // 1: state at the window's first chunk is zero (Eq. 14-15)
+  int elems;             // d*dprime + dprime
+  int s_elems;           // d*dprime
+};
+
+// ---- fused softmax + read-out + merge kernel -----------------------------------
+struct AttnArgs {
+  const bf16_t *q, *k, *v;
+  bf16_t* out;
+  const bf16_t* w1_q;
+  const float* b1_q;
+  const bf16_t* w2_q;
+  const float* b2_q;
+  const bf16_t* state_s;  // [BH, state_slots, d, dprime]
+  const float* state_z;   // [BH, state_slots, dprime]
+  float *dbg_m, *dbg_nS, *dbg_aS, *dbg_nL, *dbg_aL;
+  float scale_log2e;      // log2(e) / sqrt(d)
+  int H, T, HW, chunk, overlap;
+  int chunk0, n_win_chunks;  // chunks [chunk0, chunk0 + n_win_chunks)
+  int qtiles;                // query tiles of 256 tokens per (full) chunk
+  int state_slots;
+  int stab_mode;
+  int n_items, items_per_xcd;
+};
+
+// ---- transposes the carry into the [dprime][d] layout of the public state hook ----
+struct StateOutArgs {
+  const float* carry;  // [BH, d*dprime + dprime], S^T [d][dprime] then z
+  float* S_out;        // [BH, dprime, d]
+  float* z_out;        // [BH, dprime]
+  int BH, d, dprime;
+};
+
+hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream);
+hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream);
+hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream);
+hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream);
+
+}  // namespace rehyat

@@ -1,0 +1,69 @@
+// Prefix pass over chunk states for gfx950 (Eq. 14-18): turns the per-segment
+// partial sums written by the state kernel into the state S_t, z_t seen by each
+// chunk of the window, s_0 = z_0 = 0, s_{t+1} = s_t + (tokens that entered the
+// linear set between chunk t and chunk t+1).  Purely HBM-bound: each thread
+// owns four consecutive state elements and walks the window's chunks in order
+// (fixed summation order, so results are bit-reproducible).  S_t is written in
+// bf16, transposed ([d][D']), ready to be an MFMA operand of the read-out; z_t
+// stays fp32.  The running total is left in `carry` for the next window.
+#include "rehyat_device.h"
+#include "rehyat_kernels.h"
+
+namespace rehyat {
+
+__global__ void __launch_bounds__(256)
+prefix_kernel(PrefixArgs a) {
+  const int bh = blockIdx.y;
+  const int idx = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= a.elems) return;
+  const float* part = a.partial + (int64_t)bh * a.partial_slots * a.elems + idx;
+  float* carry = a.carry + (int64_t)bh * a.elems + idx;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if (!a.first_window) acc = *reinterpret_cast<const f32x4*>(carry);
+  const bool is_s = idx < a.s_elems;
+  for (int c = 0; c < a.n_chunks; ++c) {
+    if (is_s) {
+      u32x2 pk;
+      pk[0] = pack_bf16(acc[0], acc[1]);
+      pk[1] = pack_bf16(acc[2], acc[3]);
+      *reinterpret_cast<u32x2*>(a.state_s + ((int64_t)bh * a.state_slots + c) * a.s_elems + idx) = pk;
+    } else {
+      *reinterpret_cast<f32x4*>(a.state_z + ((int64_t)bh * a.state_slots + c) * (a.elems - a.s_elems) +
+                                (idx - a.s_elems)) = acc;
+    }
+    if (c < a.n_seg) {
+      for (int sp = 0; sp < a.nsplit; ++sp) {
+        f32x4 x = *reinterpret_cast<const f32x4*>(part + (int64_t)(c * a.nsplit + sp) * a.elems);
+        acc += x;
+      }
+    }
+  }
+  *reinterpret_cast<f32x4*>(carry) = acc;
+}
+
+__global__ void __launch_bounds__(256)
+state_out_kernel(StateOutArgs a) {
+  const int bh = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;  // index into S_out [dprime][d]
+  const int n = a.d * a.dprime;
+  const float* c = a.carry + (int64_t)bh * (n + a.dprime);
+  if (i < n) {
+    const int e = i / a.d, col = i % a.d;
+    a.S_out[(int64_t)bh * n + i] = c[col * a.dprime + e];
+  }
+  if (i < a.dprime) a.z_out[(int64_t)bh * a.dprime + i] = c[n + i];
+}
+
+hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream) {
+  dim3 grid((a.elems / 4 + 255) / 256, a.BH);
+  hipLaunchKernelGGL(prefix_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream) {
+  dim3 grid((a.d * a.dprime + 255) / 256, a.BH);
+  hipLaunchKernelGGL(state_out_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace rehyat
