@@ -1,0 +1,133 @@
+#!/usr/bin/env python3
+"""Benchmark of the hybrid-attention hot path on one MI355X.
+
+One step = one call of rehyat_forward (chunk-state kernel, prefix pass, fused
+softmax / read-out / merge kernel) on the Wan2.1-1.3B 480p single-layer shape
+(B=1, H=12, d=128, 21 latent frames x 30x52 tokens = 32,760 tokens, chunk = 1
+frame), inputs resident in HBM.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+# HBM bytes per launch of the fused attention kernel measured with rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured.
+ATTN_TRAFFIC_BYTES = None
+
+
+def algorithmic_flops(w, overlap=0):
+    """Work the method itself requires (no padding, no unused last-chunk state,
+    no phi_q / read-out for chunk 0 whose linear set is empty)."""
+    from paper_2601_04342_amd import binding
+    plan = binding.chunk_plan(w.T, w.HW, w.chunk, overlap).tolist()
+    BH, d, h, Dp = w.B * w.H, w.d, 2 * w.d, 2 * w.d
+    softmax = 4 * d * BH * sum((r[1] - r[0]) * (r[3] - r[2]) for r in plan)
+    phi_tok = 2 * (d * h + h * Dp)                      # one map, one token
+    n_lin_q = sum(r[1] - r[0] for r in plan if r[4] > 0)  # queries with a linear set
+    n_state = plan[-1][4]                               # tokens ever absorbed
+    phi_q = BH * n_lin_q * phi_tok
+    phi_k = BH * n_state * phi_tok
+    state = 2 * BH * n_state * Dp * (d + 1)
+    readout = 2 * BH * n_lin_q * Dp * (d + 1)
+    return dict(softmax=softmax, phi_q=phi_q, phi_k=phi_k, state=state, readout=readout,
+                total=softmax + phi_q + phi_k + state + readout,
+                attn_kernel=softmax + phi_q + readout, state_kernel=phi_k + state)
+
+
+def cpu_baseline(w, q, k, v, phi, heads):
+    """The fp64 oracle, as it stands, on `heads` heads of the same workload."""
+    from oracle import cref
+    qs, ks, vs = (x[:, :heads].double().numpy() for x in (q, k, v))
+    ps = {n: p[:heads].double().numpy() for n, p in phi.items()}
+    t0 = time.perf_counter()
+    cref.forward(qs, ks, vs, ps, w.T, w.HW, w.chunk)
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": w.B * w.N * (heads / w.H) / dt, "unit": "tokens/s", "cores": threads,
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"{heads} of {w.H} heads, all {w.N} tokens, fp64 C oracle (OpenMP); "
+                      "value = layer-equivalent tokens/s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="wan480p")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=12)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build is single-GPU (no sharding, no collectives); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_04342_amd import binding, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.library()   # fails loudly if the HIP library is not built
+    w = synth.WORKLOADS[args.workload]
+    q, k, v, phi = synth.make_workload(w)
+    dq, dk, dv = (x.to("cuda", torch.bfloat16).contiguous() for x in (q, k, v))
+    dphi = binding.phi_to_device(phi)
+    out = torch.empty_like(dq)
+    step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, out=out, plain=True)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    binding.profile_enable(True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    prof = binding.profile_read()
+    binding.profile_enable(False)
+    assert torch.isfinite(out.float()).all()
+
+    ms = dt * 1e3 / args.steps
+    fl = algorithmic_flops(w)
+    kern_ms = {kk: (tot / n if n else None) for kk, (tot, n) in prof.items()}
+    attn_ms = kern_ms["attn"]
+    achieved = fl["attn_kernel"] / (attn_ms * 1e-3) / 1e12
+    res = {
+        "metric": "hybrid-attn tokens/s per layer @Wan2.1-480p shape; TFLOP/s and % MFMA peak",
+        "value": w.B * w.N / (ms * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} T={w.T} HW={w.HW} "
+                               f"N={w.N} chunk={w.chunk} overlap=0 causal row-max",
+                   "phi": "hidden=D'=2d, degree 2, ReLU, N(0,0.02) seed 1",
+                   "qkv": "N(0,1) seed 0, q,k RMS-normalised, bf16"},
+        "tflops": fl["total"] / (ms * 1e-3) / 1e12,
+        "pct_mfma_peak": 100.0 * fl["total"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in fl.items()},
+        "kernel_ms": kern_ms,
+        "kernel_launches_per_step": {kk: n / args.steps for kk, (_, n) in prof.items()},
+        "workspace_bytes": binding.workspace_bytes(w.B, w.H, w.d),
+        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128>", "achieved": achieved,
+                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ATTN_TRAFFIC_BYTES},
+        "state_kernel_tflops": (fl["state_kernel"] / (kern_ms["state"] * 1e-3) / 1e12
+                                if kern_ms["state"] else None),
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, q, k, v, phi, args.cpu_heads)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

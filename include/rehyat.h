@@ -151,6 +151,19 @@ int rehyat_state(const void *k, const void *v,
                  int B, int H, int T, int HW, int d, int upto_frames,
                  void *stream);
 
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of a
+ * forward call is bracketed by HIP events recorded on the call's stream (the
+ * only stream on which the launch's duration can be observed).  Up to 4096
+ * launches are kept between reads; later ones are not timed.
+ * rehyat_profile_read waits for the recorded events, then returns for each
+ * kernel kind (0 = chunk state, 1 = prefix, 2 = fused attention) the summed
+ * duration in milliseconds and the number of launches since the last read or
+ * enable, in HOST arrays of three elements each, and clears the record.
+ */
+int rehyat_profile_enable(int on);
+int rehyat_profile_read(double *total_ms, int *launches);
+
 /* Free library-owned device memory.  Safe to call more than once. */
 int rehyat_shutdown(void);
 

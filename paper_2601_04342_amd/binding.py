@@ -20,7 +20,8 @@ STAB_ROWMAX, STAB_NONE = 0, 1
 # every symbol include/rehyat.h declares
 EXPORTS = ("rehyat_chunk_plan", "rehyat_workspace_bytes", "rehyat_set_workspace",
            "rehyat_forward", "rehyat_forward_ex", "rehyat_state", "rehyat_shutdown",
-           "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error")
+           "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error",
+           "rehyat_profile_enable", "rehyat_profile_read")
 
 
 class PhiParams(ctypes.Structure):
@@ -81,6 +82,10 @@ def _load():
     lib.rehyat_version.argtypes = []
     lib.rehyat_last_hip_error.restype = ctypes.c_char_p
     lib.rehyat_last_hip_error.argtypes = []
+    lib.rehyat_profile_enable.restype = ci
+    lib.rehyat_profile_enable.argtypes = [ci]
+    lib.rehyat_profile_read.restype = ci
+    lib.rehyat_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     _lib = lib
     return lib
 
@@ -133,6 +138,25 @@ def shutdown():
     rc = _load().rehyat_shutdown()
     if rc != OK:
         raise RehyatError(rc, "rehyat_shutdown")
+
+
+KERNEL_KINDS = ("state", "prefix", "attn")
+
+
+def profile_enable(on=True):
+    rc = _load().rehyat_profile_enable(1 if on else 0)
+    if rc != OK:
+        raise RehyatError(rc, "rehyat_profile_enable")
+
+
+def profile_read():
+    """{kind: (total_ms, launches)} since the last read; waits for the events."""
+    ms = (ctypes.c_double * 3)()
+    n = (ctypes.c_int * 3)()
+    rc = _load().rehyat_profile_read(ms, n)
+    if rc != OK:
+        raise RehyatError(rc, "rehyat_profile_read")
+    return {k: (ms[i], n[i]) for i, k in enumerate(KERNEL_KINDS)}
 
 
 def phi_to_device(phi, device="cuda"):

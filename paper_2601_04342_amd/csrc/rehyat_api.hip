@@ -34,6 +34,37 @@ int hip_fail(hipError_t e, const char* what) {
   return REHYAT_E_HIP;
 }
 
+// optional per-kernel timing with HIP events on the caller's stream
+constexpr int kProfKinds = 3;  // state, prefix, attention
+constexpr int kProfMaxPairs = 4096;
+struct Profiler {
+  bool on = false;
+  hipEvent_t beg[kProfMaxPairs], end[kProfMaxPairs];
+  int kind[kProfMaxPairs];
+  int created = 0;  // events created so far
+  int used = 0;     // pairs recorded since the last read
+};
+Profiler g_prof;
+
+struct ProfScope {
+  int slot = -1;
+  hipStream_t st;
+  ProfScope(int kind, hipStream_t s) : st(s) {
+    if (!g_prof.on || g_prof.used >= kProfMaxPairs) return;
+    if (g_prof.used >= g_prof.created) {
+      if (hipEventCreate(&g_prof.beg[g_prof.created]) != hipSuccess) return;
+      if (hipEventCreate(&g_prof.end[g_prof.created]) != hipSuccess) return;
+      ++g_prof.created;
+    }
+    slot = g_prof.used++;
+    g_prof.kind[slot] = kind;
+    (void)hipEventRecord(g_prof.beg[slot], st);
+  }
+  ~ProfScope() {
+    if (slot >= 0) (void)hipEventRecord(g_prof.end[slot], st);
+  }
+};
+
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct WsLayout {
@@ -138,6 +169,7 @@ int launch_state_window(const void* k, const void* v, const rehyat_phi_params* p
   s.partial_slots = kPartialSlots;
   s.n_items = B * H * n_seg * nsplit;
   s.items_per_xcd = (s.n_items + 7) / 8;
+  ProfScope prof(0, stream);
   hipError_t e = launch_state(s, d, s.items_per_xcd * 8, stream);
   if (e != hipSuccess) return hip_fail(e, "state kernel launch");
   return REHYAT_OK;
@@ -159,6 +191,7 @@ int launch_prefix_window(char* ws, const WsLayout& L, int B, int H, int d, int d
   p.first_window = first ? 1 : 0;
   p.elems = d * dp + dp;
   p.s_elems = d * dp;
+  ProfScope prof(1, stream);
   hipError_t e = launch_prefix(p, stream);
   if (e != hipSuccess) return hip_fail(e, "prefix kernel launch");
   return REHYAT_OK;
@@ -307,9 +340,42 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
     a.stab_mode = stab_mode;
     a.n_items = B * H * n_chunks * qtiles;
     a.items_per_xcd = (a.n_items + 7) / 8;
-    hipError_t e = launch_attn(a, d, a.items_per_xcd * 8, st);
+    hipError_t e;
+    {
+      ProfScope prof(2, st);
+      e = launch_attn(a, d, a.items_per_xcd * 8, st);
+    }
     if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
   }
+  return REHYAT_OK;
+}
+
+int rehyat_profile_enable(int on) {
+  std::lock_guard<std::mutex> lock(g_mu);
+  g_prof.on = on != 0;
+  g_prof.used = 0;
+  return REHYAT_OK;
+}
+
+int rehyat_profile_read(double* total_ms, int* launches) {
+  if (!total_ms || !launches) return REHYAT_E_NULL;
+  std::lock_guard<std::mutex> lock(g_mu);
+  for (int i = 0; i < kProfKinds; ++i) {
+    total_ms[i] = 0.0;
+    launches[i] = 0;
+  }
+  for (int i = 0; i < g_prof.used; ++i) {
+    hipError_t e = hipEventSynchronize(g_prof.end[i]);
+    float ms = 0.f;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, g_prof.beg[i], g_prof.end[i]);
+    if (e != hipSuccess) {
+      g_prof.used = 0;
+      return hip_fail(e, "profile event read");
+    }
+    total_ms[g_prof.kind[i]] += ms;
+    launches[g_prof.kind[i]] += 1;
+  }
+  g_prof.used = 0;
   return REHYAT_OK;
 }
 

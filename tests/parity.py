@@ -1,0 +1,91 @@
+"""Shared helpers of the GPU parity tests: run the library and the CPU oracle on
+the same seeded, bf16-rounded inputs and compare element by element."""
+import numpy as np
+import torch
+
+from oracle import cref
+from paper_2601_04342_amd import binding, synth
+
+# Tolerances.  Output: the bar the operator is held to (bf16 inputs, fp32
+# accumulation, bf16 output): max-abs 1e-2 and mean-abs 1e-3.
+OUT_MAX_ABS = 1e-2
+OUT_MEAN_ABS = 1e-3
+# Components (fp32 on the GPU): the row maximum and the softmax sum come from
+# fp32 products of exactly represented bf16 values; the linear terms pass twice
+# through a bf16 rounding (hidden layer, features: 2^-9 relative each) and the
+# state S_t is rounded to bf16 once.
+M_ABS = 2e-5
+NS_REL = 2e-5
+NL_REL = 1e-2
+AVG_ABS = 1e-2   # aS/nS and aL/nL are weighted averages of v, scale O(1)
+
+
+def to_device(q, k, v, phi):
+    dq, dk, dv = (x.to("cuda", torch.bfloat16).contiguous() for x in (q, k, v))
+    return dq, dk, dv, binding.phi_to_device(phi)
+
+
+def oracle_inputs(q, k, v, phi, heads=None, batch=None):
+    """fp64 numpy views of the same values, optionally a subset of heads."""
+    if batch is not None:
+        q, k, v = q[batch:batch + 1], k[batch:batch + 1], v[batch:batch + 1]
+    if heads is not None:
+        q, k, v = q[:, heads], k[:, heads], v[:, heads]
+        phi = {n: p[heads] for n, p in phi.items()}
+    return (q.double().numpy(), k.double().numpy(), v.double().numpy(),
+            {n: p.double().numpy() for n, p in phi.items()})
+
+
+def compare(out, comps, ref, stab=0, rows=None, label=""):
+    """out/comps: GPU results already restricted to the oracle's (b, h) subset,
+    full token axis; ref: oracle Components on `rows` (None = all)."""
+    sel = slice(None) if rows is None else rows
+    o = out.float().cpu().double().numpy()[:, :, sel]
+    assert np.isfinite(o).all(), label
+    err = np.abs(o - ref.out)
+    assert err.max() <= OUT_MAX_ABS, (label, "out max-abs", err.max())
+    assert err.mean() <= OUT_MEAN_ABS, (label, "out mean-abs", err.mean())
+    if comps is None:
+        return err.max(), err.mean()
+    c = {n: t.cpu().double().numpy()[:, :, sel] for n, t in comps.items()}
+    assert np.abs(c["m"] - ref.m).max() <= M_ABS * max(1.0, np.abs(ref.m).max()), label
+    # the library reports softmax terms relative to exp(-m) in both modes, and
+    # with the stabiliser off the linear terms multiplied by exp(-m)
+    if stab == 0:
+        nS, aS, nL, aL = ref.nS, ref.aS, ref.nL, ref.aL
+    else:
+        sc = np.exp(-ref.m)
+        nS, aS = ref.nS * sc, ref.aS * sc[..., None]
+        nL, aL = ref.nL * sc, ref.aL * sc[..., None]
+    assert (np.abs(c["nS"] - nS) <= NS_REL * nS).all(), (label, "nS")
+    assert (np.abs(c["nL"] - nL) <= NL_REL * nL + 1e-30).all(), (label, "nL")
+    assert np.abs(c["aS"] / c["nS"][..., None] - aS / nS[..., None]).max() <= AVG_ABS, (label, "aS")
+    has_l = nL > 0
+    if has_l.any():
+        g = c["aL"][has_l] / c["nL"][has_l][..., None]
+        r = aL[has_l] / nL[has_l][..., None]
+        assert np.abs(g - r).max() <= AVG_ABS, (label, "aL")
+    assert (c["nL"][~has_l] == 0).all() and (c["aL"][~has_l] == 0).all(), (label, "empty linear set")
+    return err.max(), err.mean()
+
+
+def linear_share(ref, stab=0):
+    nL = ref.nL if stab == 0 else ref.nL * np.exp(-ref.m)
+    nS = ref.nS if stab == 0 else ref.nS * np.exp(-ref.m)
+    return float((nL / (nS + nL)).mean())
+
+
+def run_case(B, H, T, HW, d, chunk, overlap=0, stab=0, gain=1.0, rms=True, seed=0,
+             debug=True, phi=None):
+    N = T * HW
+    q, k, v = synth.make_qkv(B, H, N, d, seed=seed, rms_norm=rms)
+    if phi is None:
+        phi = synth.make_phi(H, d, seed=seed + 1, gain=gain)
+    dq, dk, dv, dphi = to_device(q, k, v, phi)
+    res = binding.forward(dq, dk, dv, dphi, T, HW, chunk, overlap=overlap, stab_mode=stab,
+                          debug=debug)
+    torch.cuda.synchronize()
+    out, comps = res if debug else (res, None)
+    ref = cref.forward(*oracle_inputs(q, k, v, phi), T, HW, chunk, overlap=overlap, stab=stab)
+    label = f"B{B} H{H} T{T} HW{HW} d{d} chunk{chunk} ov{overlap} stab{stab} gain{gain}"
+    return compare(out, comps, ref, stab=stab, label=label), ref

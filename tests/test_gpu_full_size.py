@@ -1,0 +1,121 @@
+"""GPU parity at the full benchmark shapes, in the launch configuration the
+benchmark times (plain rehyat_forward, library-owned workspace).  The oracle
+evaluates sampled query rows of sampled heads one by one (chunk-recurrent
+form); properties that hold at any size cover the rest."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cref
+from paper_2601_04342_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(w, overlap=0, n_random=24, seed=0):
+    plan = cref.chunk_plan(w.T, w.HW, w.chunk, overlap)
+    rows = set()
+    for t in (0, 1, len(plan) // 2, len(plan) - 1):
+        q_lo, q_hi = int(plan[t, 0]), int(plan[t, 1])
+        rows.update([q_lo, q_lo + 255, q_lo + 256, q_hi - 1])   # tile and chunk edges
+    rng = np.random.default_rng(seed)
+    rows.update(int(x) for x in rng.integers(0, w.N, n_random))
+    return np.array(sorted(r for r in rows if 0 <= r < w.N), dtype=np.int64)
+
+
+def check_workload(name, heads, batches=(0,), overlap=0, debug=False, gain=1.0):
+    w = synth.WORKLOADS[name]
+    print(f"[gpu-test] full size {name} heads {heads} batches {batches} gain {gain}", flush=True)
+    q, k, v, phi = synth.make_workload(w, gain=gain)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    if overlap == 0 and not debug:
+        out, comps = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, plain=True), None
+    else:
+        res = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, overlap=overlap, debug=debug)
+        out, comps = res if debug else (res, None)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    rows = sample_rows(w, overlap)
+    worst = (0.0, 0.0)
+    for b in batches:
+        for h in heads:
+            ref = cref.forward(*parity.oracle_inputs(q, k, v, phi, heads=[h], batch=b),
+                               w.T, w.HW, w.chunk, overlap=overlap, rows=rows)
+            c = None if comps is None else {n: t[b:b + 1, h:h + 1] for n, t in comps.items()}
+            e = parity.compare(out[b:b + 1, h:h + 1], c, ref, rows=rows, label=f"{name} b{b} h{h}")
+            worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+            print(f"   b{b} h{h}: max-abs {e[0]:.2e} mean-abs {e[1]:.2e} "
+                  f"linear share {parity.linear_share(ref):.2f}", flush=True)
+    return out, worst
+
+
+def test_wan480p_sampled_rows_with_components():
+    check_workload("wan480p", heads=[0, 11], debug=True)
+
+
+def test_wan480p_bench_configuration():
+    check_workload("wan480p", heads=[5])
+
+
+def test_wan480p_balanced_linear_share():
+    """phi scaled so softmax and linear parts carry comparable weight."""
+    check_workload("wan480p", heads=[3], gain=0.35, debug=True)
+
+
+@pytest.mark.parametrize("name", ["wan480p_cfg_c1", "wan480p_cfg_c2", "wan480p_cfg_c3"])
+def test_cfg_pair_chunk_sweep(name):
+    check_workload(name, heads=[7], batches=(0, 1))
+
+
+def test_wan480p_overlap_one_frame():
+    """T_c = 3, T_o = 1: the setting of the paper's best models (Table 1)."""
+    check_workload("wan480p_cfg_c3", heads=[2], batches=(1,), overlap=1)
+
+
+def test_long_video_flat_workspace():
+    """Doubling the latent frames leaves the workspace untouched (section 3.3,
+    point 3): the same caller-owned buffer serves T=21 and T=41, the library
+    allocates nothing, and guard bands around it stay intact."""
+    w21, w41 = synth.WORKLOADS["wan480p"], synth.WORKLOADS["wan480p_long"]
+    need = binding.workspace_bytes(w41.B, w41.H, w41.d)
+    assert need == binding.workspace_bytes(w21.B, w21.H, w21.d)
+    guard = 1 << 16
+    buf = torch.full((need + 2 * guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    binding.shutdown()
+    try:
+        binding.set_workspace(buf[guard:guard + need])
+        torch.cuda.synchronize()
+        free_before = None
+        for name in ("wan480p", "wan480p_long"):
+            out, _ = check_workload(name, heads=[9])
+            del out
+            torch.cuda.synchronize()
+        q, k, v, phi = synth.make_workload(w41)
+        dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+        out = torch.empty_like(dq)
+        torch.cuda.synchronize()
+        free_before = torch.cuda.mem_get_info()[0]
+        binding.forward(dq, dk, dv, dphi, w41.T, w41.HW, w41.chunk, out=out, plain=True)
+        torch.cuda.synchronize()
+        assert torch.cuda.mem_get_info()[0] == free_before   # nothing allocated by the call
+    finally:
+        binding.set_workspace(None)
+    assert (buf[:guard] == 0xA5).all() and (buf[guard + need:] == 0xA5).all()
+
+
+def test_wan720p_and_full_softmax_comparison():
+    """720p shape; the same inputs through one chunk covering all tokens are
+    plain softmax attention (Eq. 2), checked on sampled rows."""
+    w = synth.WORKLOADS["wan720p"]
+    out, _ = check_workload("wan720p", heads=[4])
+    q, k, v, phi = synth.make_workload(w)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    full = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.T, plain=True)
+    torch.cuda.synchronize()
+    rows = np.random.default_rng(1).integers(0, w.N, 16)
+    h = 4
+    qs = q[0, h, rows].double()
+    want = torch.softmax(qs @ k[0, h].double().T / np.sqrt(w.d), dim=-1) @ v[0, h].double()
+    err = (full[0, h, rows].float().cpu().double() - want).abs()
+    assert err.max() <= parity.OUT_MAX_ABS and err.mean() <= parity.OUT_MEAN_ABS
