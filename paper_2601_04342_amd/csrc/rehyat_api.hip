@@ -297,7 +297,8 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
   int win = kPartialSlots / nsplit;
   if (win > kStateSlots) win = kStateSlots;
   const int chunk_frames = chunk < T ? chunk : T;
-  const int qtiles = (int)(((int64_t)chunk_frames * HW + 255) / 256);
+  const int qtile = attn_query_tile(d);
+  const int qtiles = (int)(((int64_t)chunk_frames * HW + qtile - 1) / qtile);
 
   for (int c0 = 0; c0 < nc; c0 += win) {
     const int c1 = (c0 + win < nc) ? c0 + win : nc;

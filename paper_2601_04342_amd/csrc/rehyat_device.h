@@ -130,7 +130,7 @@ struct TileRegs {
   u32x4 v[NV];
 };
 
-template <int ROWS, int COLS, int NT>
+template <int ROWS, int COLS, int NT, bool CHECK>
 __device__ __forceinline__ void tile_load(TileRegs<ROWS, COLS, NT>& regs, const bf16_t* src,
                                           int64_t src_ld, int valid_rows, int tid) {
   constexpr int VPR = COLS / 8;
@@ -140,7 +140,8 @@ __device__ __forceinline__ void tile_load(TileRegs<ROWS, COLS, NT>& regs, const 
     const int row = vi / VPR;
     const int cv = vi % VPR;
     u32x4 x = {0u, 0u, 0u, 0u};
-    if (row < ROWS && row < valid_rows)
+    constexpr bool exact = (ROWS * VPR) % NT == 0;  // no thread runs past the tile
+    if ((exact || row < ROWS) && (!CHECK || row < valid_rows))
       x = *reinterpret_cast<const u32x4*>(src + (int64_t)row * src_ld + cv * 8);
     regs.v[n] = x;
   }
@@ -174,6 +175,27 @@ __device__ __forceinline__ void tile_store(const TileRegs<ROWS, COLS, NT>& regs,
       }
     }
   }
+}
+
+// Combine a per-lane value across the two 32-lane halves of the wave with
+// v_permlane32_swap: it exchanges the high half of its first register with the
+// low half of its second, so starting from two copies of x one register ends
+// up holding the low half's values in all lanes and the other the high half's.
+// Written as inline asm with both registers read-write (the compiler builtin
+// loses track of the second result when both inputs are copies of one value);
+// the leading s_nop covers the VALU-write -> permlane-read hazard.
+__device__ __forceinline__ void half_swap(float& a, float& b) {
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float half_swap_max(float x) {
+  float a = x, b = x;
+  half_swap(a, b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float half_swap_sum(float x) {
+  float a = x, b = x;
+  half_swap(a, b);
+  return a + b;
 }
 
 // Workgroup index -> logical work item so that consecutive logical items run

@@ -59,7 +59,7 @@ struct AttnArgs {
   float scale_log2e;      // log2(e) / sqrt(d)
   int H, T, HW, chunk, overlap;
   int chunk0, n_win_chunks;  // chunks [chunk0, chunk0 + n_win_chunks)
-  int qtiles;                // query tiles of 256 tokens per (full) chunk
+  int qtiles;                // query tiles per (full) chunk
   int state_slots;
   int stab_mode;
   int n_items, items_per_xcd;
@@ -76,6 +76,7 @@ struct StateOutArgs {
 hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream);
 hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream);
 hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream);
+int attn_query_tile(int d);  // query tokens per workgroup of the attention kernel
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream);
 
 }  // namespace rehyat

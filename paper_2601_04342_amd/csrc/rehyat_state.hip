@@ -71,7 +71,7 @@ state_kernel(StateArgs a) {
 #pragma unroll
     for (int sl = 0; sl < HID / 64; ++sl) {
       TileRegs<64, D, NT> w;
-      tile_load<64, D, NT>(w, W1 + (int64_t)sl * 64 * D, D, 64, tid);
+      tile_load<64, D, NT, false>(w, W1 + (int64_t)sl * 64 * D, D, 64, tid);
       tile_store<64, D, NT, false>(w, W1s + sl * 64 * LDX, LDX, tid);
     }
     for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_k[(int64_t)h * HID + i];
@@ -103,8 +103,8 @@ state_kernel(StateArgs a) {
   TileRegs<64, D, NT> kreg, vreg;
   if (lo < hi) {
     int valid = (int)((hi - lo) < 64 ? (hi - lo) : 64);
-    tile_load<64, D, NT>(kreg, Kg + lo * D, D, valid, tid);
-    tile_load<64, D, NT>(vreg, Vg + lo * D, D, valid, tid);
+    tile_load<64, D, NT, true>(kreg, Kg + lo * D, D, valid, tid);
+    tile_load<64, D, NT, true>(vreg, Vg + lo * D, D, valid, tid);
   }
   for (int64_t t0 = lo; t0 < hi; t0 += 64) {
     __syncthreads();  // previous tile consumed (also orders the W1 / bias staging)
@@ -114,8 +114,8 @@ state_kernel(StateArgs a) {
     if (t0 + 64 < hi) {
       int64_t rem = hi - (t0 + 64);
       int valid = (int)(rem < 64 ? rem : 64);
-      tile_load<64, D, NT>(kreg, Kg + (t0 + 64) * D, D, valid, tid);
-      tile_load<64, D, NT>(vreg, Vg + (t0 + 64) * D, D, valid, tid);
+      tile_load<64, D, NT, true>(kreg, Kg + (t0 + 64) * D, D, valid, tid);
+      tile_load<64, D, NT, true>(vreg, Vg + (t0 + 64) * D, D, valid, tid);
     }
     // ---- U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden]
 #pragma unroll
