@@ -1,8 +1,8 @@
 // Fused hybrid-attention output kernel for gfx950.
 //
-// One workgroup (4 waves) owns 256 consecutive query tokens of one chunk of one
-// (batch, head); each wave owns 64 of them and keeps, per query, the running
-// softmax maximum and sum and the d-wide numerator in MFMA accumulators.
+// One workgroup (4 waves) owns 32*QB*4 consecutive query tokens of one chunk of
+// one (batch, head); each wave owns 32*QB of them and keeps, per query, the
+// running softmax maximum and sum and the d-wide numerator in MFMA accumulators.
 //
 //   phase S (Eq. 6, 8): exponents K Q^T over the chunk's softmax window
 //            (Eq. 12), online maximum/sum, numerator V^T P.
@@ -16,7 +16,13 @@
 // Everything is computed transposed (keys / features in accumulator rows,
 // queries in lanes) so that per-query statistics live in one lane and each
 // product's accumulator is directly the B operand of the next product.
+//
+// All operands that are shared by the four waves (K and V tiles, then W1, W2
+// and the chunk state) travel global -> LDS with direct loads into four LDS
+// tile buffers, issued one or more steps ahead of their use.
 #include <cstdlib>
+#include <type_traits>
+#include <utility>
 
 #include "rehyat_device.h"
 #include "rehyat_kernels.h"
@@ -40,18 +46,12 @@ struct AttnShape {
   static constexpr int QW = 32 * QB;   // queries per wave
   static constexpr int QT = 4 * QW;    // queries per workgroup
   static constexpr int KT = 64;        // keys per tile
-  static constexpr int TILE_BYTES = 64 * D * 2;  // one K or V tile in LDS (unpadded, chunk-swizzled)
-  // phase L tiles (padded rows, staged through registers)
-  static constexpr int LDK = D + 8;    // W1 slab row stride
-  static constexpr int LDW2 = HID + 8; // W2 slab row stride
-  static constexpr int LDS_S = 32 + 8; // state slab row stride
-  static constexpr int BUFA = (64 * LDK > 32 * LDW2) ? 64 * LDK : 32 * LDW2;  // elements
-  static constexpr int BUFB = D * LDS_S;
-  static_assert(BUFA * 2 <= 2 * TILE_BYTES && BUFB * 2 <= 2 * TILE_BYTES, "phase L tiles alias the K/V tiles");
+  static constexpr int TILE_BYTES = 64 * D * 2;  // one LDS tile: 64 rows of 2D bytes
+  static constexpr int LPT = TILE_BYTES / 4096;  // direct-load instructions per wave per tile
 };
 
 // ---------------------------------------------------------------------------
-// K/V tiles in LDS: [64 rows][D] bf16 with unpadded rows, filled by direct
+// LDS tiles are [rows][ROWBYTES] with unpadded rows, filled by direct
 // global->LDS loads (each wave instruction moves 1 KB to consecutive LDS
 // bytes, so rows cannot be padded).  Bank conflicts are avoided by permuting
 // the 16-byte chunks of a row: chunk c of row `row` is stored at chunk position
@@ -59,65 +59,48 @@ struct AttnShape {
 // touches together (16 consecutive rows, same chunk) onto chunk positions, and
 // it also separates the 4 consecutive rows that one transposing read touches.
 // ---------------------------------------------------------------------------
-template <int D>
+template <int ROWBYTES>
 __device__ __forceinline__ int swz(int row) {
-  if (D == 128) return ((row & 3) << 2) | ((row >> 2) & 3);   // 16 chunks per 256-byte row
-  return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);           // 8 chunks per 128-byte row
+  if (ROWBYTES == 256) return ((row & 3) << 2) | ((row >> 2) & 3);   // 16 chunks per row
+  return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);                  // 128-byte rows, 8 chunks
 }
 
-// byte offset of element (row, col) inside a tile
-template <int D>
+// byte offset of element (row, col) inside a tile whose rows hold ROWBYTES/2 bf16
+template <int ROWBYTES>
 __device__ __forceinline__ int tile_off(int row, int col) {
-  return row * (2 * D) + ((((col >> 3) ^ swz<D>(row)) << 4) | ((col & 7) << 1));
+  return row * ROWBYTES + ((((col >> 3) ^ swz<ROWBYTES>(row)) << 4) | ((col & 7) << 1));
 }
 
-// Direct loads of one 64-row tile: wave w moves the 1 KB blocks w, w+4, ...
-// Lane i of a block fills LDS chunk slot i, so it fetches the global chunk that
-// the swizzle assigns to that slot; swz depends on the row modulo 16 only, so a
-// lane's byte offset inside the tile is `lane_off` for its first block and
-// grows by 4096 per further block.
-template <int D>
-__device__ __forceinline__ int tile_lane_offset(int wave, int lane) {
-  constexpr int CPR = D / 8;     // 16-byte chunks per row
-  constexpr int RPB = 64 / CPR;  // rows per 1 KB block
-  const int row = wave * RPB + lane / CPR;
-  const int c = (lane % CPR) ^ swz<D>(row);
-  return row * (2 * D) + c * 16;
-}
-
-template <int D>
-__device__ __forceinline__ void tile_load_direct(const char* gtile, char* lds_tile, int lane_off, int wave) {
-  constexpr int NBLK = (64 * 2 * D) / 1024;  // 1 KB blocks per tile
+// Direct loads of one tile.  Wave w moves the 1 KB blocks w, w+4, ...; lane i of
+// a block fills LDS chunk slot i, so it fetches the global chunk that the
+// swizzle assigns to that slot.  `rowaddr(R)` gives the byte offset, from
+// `gbase`, of the global row segment that becomes tile row R.
+template <int ROWBYTES, int TILE_BYTES, typename RowAddr>
+__device__ __forceinline__ void tile_load_direct(const char* gbase, char* lds_tile, int wave, int lane,
+                                                 RowAddr rowaddr) {
+  constexpr int CPR = ROWBYTES / 16;     // chunks per row
+  constexpr int RPB = 1024 / ROWBYTES;   // rows per 1 KB block
+  constexpr int NBLK = TILE_BYTES / 1024;
 #pragma unroll
   for (int n = 0; n < NBLK / 4; ++n) {
-    const char* src = gtile + (uint32_t)(lane_off + n * 4096);
+    const int blk = wave + 4 * n;
+    const int R = blk * RPB + lane / CPR;
+    const int c = (lane % CPR) ^ swz<ROWBYTES>(R);
+    const char* src = gbase + (uint32_t)(rowaddr(R) + c * 16);
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)(lds_tile + (wave + 4 * n) * 1024),
-                                     16, 0, 0);
+                                     (__attribute__((address_space(3))) void*)(lds_tile + blk * 1024), 16, 0, 0);
   }
 }
 
-// Same for a tile with only `valid_rows` rows in bounds: rows beyond re-read the
-// last valid row (finite values; their keys are masked in the softmax).
-template <int D>
-__device__ __forceinline__ void tile_load_direct_tail(const char* gtile, char* lds_tile, int valid_rows,
-                                                      int wave, int lane) {
-  constexpr int CPR = D / 8;
-  constexpr int RPB = 64 / CPR;
-  constexpr int NBLK = (64 * 2 * D) / 1024;
-#pragma unroll
-  for (int n = 0; n < NBLK / 4; ++n) {
-    const int j = wave + 4 * n;
-    const int row = j * RPB + lane / CPR;
-    const int c = (lane % CPR) ^ swz<D>(row);
-    const int grow = row < valid_rows ? row : valid_rows - 1;
-    const char* src = gtile + (uint32_t)(grow * (2 * D) + c * 16);
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                     (__attribute__((address_space(3))) void*)(lds_tile + j * 1024), 16, 0, 0);
-  }
+// Wait until at most N of this wave's direct loads are outstanding (and all of
+// its LDS accesses are done), then workgroup barrier.  Written as one asm block:
+// the compiler's own barrier would wait for every outstanding direct load and
+// so serialise the prefetch with the computation.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
 }
-
-// per-lane byte offsets of the fragment reads inside a tile
+// per-lane byte offsets of the fragment reads inside a K / V tile
 template <int D>
 struct FragOffsets {
   int k[D / 16];        // A fragment of K rows r (+32 per key block), k-step ks
@@ -130,12 +113,12 @@ __device__ __forceinline__ FragOffsets<D> make_frag_offsets(int lane) {
   FragOffsets<D> f;
   const int g = lane >> 5, r = lane & 31, i = lane & 15;
 #pragma unroll
-  for (int ks = 0; ks < D / 16; ++ks) f.k[ks] = tile_off<D>(r, 16 * ks + 8 * g);
+  for (int ks = 0; ks < D / 16; ++ks) f.k[ks] = tile_off<2 * D>(r, 16 * ks + 8 * g);
 #pragma unroll
   for (int db = 0; db < D / 32; ++db) {
     const int col = 32 * db + 16 * (r >> 4) + 4 * (i & 3);
-    f.v_lo[db] = tile_off<D>(4 * g + (i >> 2), col);
-    f.v_hi[db] = tile_off<D>(8 + 4 * g + (i >> 2), col);
+    f.v_lo[db] = tile_off<2 * D>(4 * g + (i >> 2), col);
+    f.v_hi[db] = tile_off<2 * D>(8 + 4 * g + (i >> 2), col);
   }
   return f;
 }
@@ -251,15 +234,99 @@ __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, con
   }
 }
 
+// ---------------------------------------------------------------------------
+// Phase L operand tiles and the order in which they stream through the four
+// LDS tile buffers.  Tile kinds:
+//   W1 tile j : W1 rows [64j, 64j+64), rows of 2D bytes (contiguous in memory)
+//   W2 tile pb: W2 rows [32pb, 32pb+32); tile rows 0..31 hold their first k-half
+//               (2D bytes), tile rows 32..63 the second
+//   S tile pp : S_t^T columns [64pp, 64pp+64) of all D rows, rows of 128 bytes
+// A step needs its tiles landed (at most `younger` tiles issued after them may
+// still be in flight) and, after its barrier, issues up to two further tiles
+// into buffers whose last readers have passed that barrier.
+// ---------------------------------------------------------------------------
+struct LinStep {
+  int younger;        // tiles that may still be in flight when the step starts
+  int n_issue;        // tiles issued after the step's barrier
+  int kind[2], idx[2], buf[2];
+  int buf_w, buf_s;   // buffers read by the step (W1 or W2 tile; S tile)
+};
+enum { kW1 = 0, kW2 = 1, kS = 2 };
+
+template <int D>
+struct LinSched;
+template <>
+struct LinSched<128> {   // 4 W1 steps, then 8 feature-block steps
+  static constexpr int NPRO = 4;
+  static constexpr LinStep pro(int i) { return LinStep{0, 1, {kW1, 0}, {i, 0}, {i, 0}, 0, 0}; }
+  static constexpr LinStep step(int st) {
+    switch (st) {
+      case 0: return LinStep{3, 0, {0, 0}, {0, 0}, {0, 0}, 0, 0};
+      case 1: return LinStep{2, 1, {kS, 0}, {0, 0}, {0, 0}, 1, 0};
+      case 2: return LinStep{2, 1, {kW2, 0}, {0, 0}, {1, 0}, 2, 0};
+      case 3: return LinStep{2, 1, {kW2, 0}, {1, 0}, {2, 0}, 3, 0};
+      case 4: return LinStep{1, 1, {kS, 0}, {1, 0}, {3, 0}, 1, 0};
+      case 5: return LinStep{1, 1, {kW2, 0}, {2, 0}, {1, 0}, 2, 0};
+      case 6: return LinStep{0, 2, {kW2, kS}, {3, 2}, {2, 0}, 1, 3};
+      case 7: return LinStep{1, 1, {kW2, 0}, {4, 0}, {1, 0}, 2, 3};
+      case 8: return LinStep{0, 2, {kW2, kS}, {5, 3}, {2, 3}, 1, 0};
+      case 9: return LinStep{1, 1, {kW2, 0}, {6, 0}, {1, 0}, 2, 0};
+      case 10: return LinStep{0, 1, {kW2, 0}, {7, 0}, {2, 0}, 1, 3};
+      default: return LinStep{0, 0, {0, 0}, {0, 0}, {0, 0}, 2, 3};
+    }
+  }
+};
+template <>
+struct LinSched<64> {    // 2 W1 steps, then 4 feature-block steps
+  static constexpr int NPRO = 4;
+  static constexpr LinStep pro(int i) {
+    switch (i) {
+      case 0: return LinStep{0, 1, {kW1, 0}, {0, 0}, {0, 0}, 0, 0};
+      case 1: return LinStep{0, 1, {kW1, 0}, {1, 0}, {1, 0}, 0, 0};
+      case 2: return LinStep{0, 1, {kS, 0}, {0, 0}, {2, 0}, 0, 0};
+      default: return LinStep{0, 1, {kW2, 0}, {0, 0}, {3, 0}, 0, 0};
+    }
+  }
+  static constexpr LinStep step(int st) {
+    switch (st) {
+      case 0: return LinStep{3, 0, {0, 0}, {0, 0}, {0, 0}, 0, 0};
+      case 1: return LinStep{2, 1, {kW2, 0}, {1, 0}, {0, 0}, 1, 0};
+      case 2: return LinStep{1, 1, {kS, 0}, {1, 0}, {1, 0}, 3, 2};
+      case 3: return LinStep{1, 1, {kW2, 0}, {2, 0}, {3, 0}, 0, 2};
+      case 4: return LinStep{0, 1, {kW2, 0}, {3, 0}, {0, 0}, 3, 1};
+      default: return LinStep{0, 0, {0, 0}, {0, 0}, {0, 0}, 0, 1};
+    }
+  }
+};
+
+template <int D, int ST>
+struct LinStepC { static constexpr LinStep value = LinSched<D>::step(ST); };
+template <int D, int I>
+struct LinProC { static constexpr LinStep value = LinSched<D>::pro(I); };
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
 template <int D, int QB>
 __global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1))
 attn_kernel(AttnArgs a) {
   using C = AttnShape<D, QB>;
   constexpr int HID = C::HID, DP = C::DP, KS = C::KS, DB = C::DB, NT = C::NT;
-  // K tiles (two buffers) then V tiles (two buffers); phase L reuses the memory
-  __shared__ __attribute__((aligned(1024))) char smem[4 * C::TILE_BYTES];
-  bf16_t* const bufA = reinterpret_cast<bf16_t*>(smem);                       // phase L: W1 / W2 slabs
-  bf16_t* const bufB = reinterpret_cast<bf16_t*>(smem + 2 * C::TILE_BYTES);   // phase L: state slabs
+  constexpr int TB = C::TILE_BYTES, LPT = C::LPT;
+  // Four tile buffers, declared as separate objects so that a pending direct
+  // load into one of them does not make the compiler wait before reads of
+  // another.  Phase S: K tiles in A0/A1, V tiles in A2/A3 (even/odd tile).
+  __shared__ __attribute__((aligned(1024))) char A0[TB];
+  __shared__ __attribute__((aligned(1024))) char A1[TB];
+  __shared__ __attribute__((aligned(1024))) char A2[TB];
+  __shared__ __attribute__((aligned(1024))) char A3[TB];
   __shared__ __attribute__((aligned(16))) float sb1[HID];
   __shared__ __attribute__((aligned(16))) float sb2[DP];
   __shared__ __attribute__((aligned(16))) float sz[DP];
@@ -288,6 +355,18 @@ attn_kernel(AttnArgs a) {
   const bf16_t* Kg = a.k + (int64_t)bh * N * D;
   const bf16_t* Vg = a.v + (int64_t)bh * N * D;
   bf16_t* Og = a.out + (int64_t)bh * N * D;
+  const bool has_linear = cr.l_hi > 0 && !(a.exp_flags & 2);
+
+  // ---- per-head vectors of phase L go to LDS first: their loads must be older
+  // than every direct load so that the counted waits below see only tile loads
+  if (has_linear) {
+    const float* zt = a.state_z + ((int64_t)bh * a.state_slots + tc) * DP;
+    for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_q[(int64_t)h * HID + i];
+    for (int i = tid; i < DP; i += NT) {
+      sb2[i] = a.b2_q[(int64_t)h * DP + i];
+      sz[i] = zt[i];
+    }
+  }
 
   // ---- queries of this wave, held as B operands ---------------------------
   const int64_t qw0 = q0 + wave * C::QW;
@@ -310,53 +389,57 @@ attn_kernel(AttnArgs a) {
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) O[db][qb][e] = 0.f;
-  float mrun[QB];  // running max of exponent * log2(e)
+  float mrun[QB];  // running max of exponent * log2(e)/sqrt(d)
   float lrun[QB];  // this lane half's share of the sum
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     mrun[qb] = -INFINITY;
     lrun[qb] = 0.f;
   }
-
-  const float sc = a.scale_log2e;  // log2(e)/sqrt(d): mrun holds exponent * sc
+  const float sc = a.scale_log2e;
 
   // =========================== phase S =====================================
   {
     const FragOffsets<D> fo = make_frag_offsets<D>(lane);
-    const int lane_off = tile_lane_offset<D>(wave, lane);
     const int64_t s_lo = cr.s_lo, s_hi = cr.s_hi;
-    const int n_full = (int)((s_hi - s_lo) / 64);
-    const int rem = (int)((s_hi - s_lo) - 64 * (int64_t)n_full);  // keys in the ragged last tile
-    char* const Kt = smem;
-    char* const Vt = smem + 2 * C::TILE_BYTES;
+    const int n_full = (a.exp_flags & 1) ? 1 : (int)((s_hi - s_lo) / 64);
+    const int rem = (int)((s_hi - s_lo) - 64 * (int64_t)((s_hi - s_lo) / 64));  // keys in the ragged last tile
     const char* const Kb = reinterpret_cast<const char*>(Kg + s_lo * D);
     const char* const Vb = reinterpret_cast<const char*>(Vg + s_lo * D);
-    if (n_full > 0) {
-      tile_load_direct<D>(Kb, Kt, lane_off, wave);
-      tile_load_direct<D>(Vb, Vt, lane_off, wave);
-    }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the tile has landed in LDS
-    __syncthreads();
-    for (int it = 0; it < n_full; ++it) {
-      // Tile it+1 goes into the other buffer, whose last readers (tile it-1) all
-      // passed the barrier that ended the previous iteration.
+    auto contiguous = [](int R) { return R * (2 * D); };
+    // K and V of tile `it` into the given buffers
+    auto issue_kv = [&](int it, char* kd, char* vd) {
+      const int64_t goff = (int64_t)it * TB;
+      tile_load_direct<2 * D, TB>(Kb + goff, kd, wave, lane, contiguous);
+      tile_load_direct<2 * D, TB>(Vb + goff, vd, wave, lane, contiguous);
+    };
+    if (n_full > 0) issue_kv(0, A0, A2);
+    wait_loads_and_barrier<0>();   // also publishes the bias vectors
+    // Two tiles per trip so that buffer choice is static.  The loads of tile
+    // it+1 go into the other buffer pair, whose last readers (tile it-1) all
+    // passed the barrier that ended the previous tile; they must have landed,
+    // for every wave, by the barrier that ends tile it.
+    for (int it = 0; it < n_full; it += 2) {
+      if (it + 1 < n_full) issue_kv(it + 1, A1, A3);
+      softmax_tile<D, QB, false>(A0, A2, fo, Qr, O, mrun, lrun, sc, 64, lane);
+      wait_loads_and_barrier<0>();
       if (it + 1 < n_full) {
-        const int64_t goff = (int64_t)(it + 1) * C::TILE_BYTES;
-        tile_load_direct<D>(Kb + goff, Kt + ((it + 1) & 1) * C::TILE_BYTES, lane_off, wave);
-        tile_load_direct<D>(Vb + goff, Vt + ((it + 1) & 1) * C::TILE_BYTES, lane_off, wave);
+        if (it + 2 < n_full) issue_kv(it + 2, A0, A2);
+        softmax_tile<D, QB, false>(A1, A3, fo, Qr, O, mrun, lrun, sc, 64, lane);
+        wait_loads_and_barrier<0>();
       }
-      softmax_tile<D, QB, false>(Kt + (it & 1) * C::TILE_BYTES, Vt + (it & 1) * C::TILE_BYTES, fo, Qr, O,
-                                 mrun, lrun, sc, 64, lane);
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
     }
-    if (rem > 0) {  // ragged last tile, outside the loop so that its index math is not kept live in it
-      const int64_t goff = (int64_t)n_full * C::TILE_BYTES;
-      tile_load_direct_tail<D>(Kb + goff, Kt, rem, wave, lane);
-      tile_load_direct_tail<D>(Vb + goff, Vt, rem, wave, lane);
-      __builtin_amdgcn_s_waitcnt(0x0F70);
-      __syncthreads();
-      softmax_tile<D, QB, true>(Kt, Vt, fo, Qr, O, mrun, lrun, sc, rem, lane);
+    if (rem > 0) {
+      // ragged last tile, outside the loop so that its index math is not kept
+      // live in it; rows beyond the window re-read the last valid row (finite
+      // values) and their keys are masked
+      const int64_t goff = (int64_t)((s_hi - s_lo) / 64) * TB;
+      auto clamped = [rem](int R) { return (R < rem ? R : rem - 1) * (2 * D); };
+      tile_load_direct<2 * D, TB>(Kb + goff, A0, wave, lane, clamped);
+      tile_load_direct<2 * D, TB>(Vb + goff, A2, wave, lane, clamped);
+      wait_loads_and_barrier<0>();
+      softmax_tile<D, QB, true>(A0, A2, fo, Qr, O, mrun, lrun, sc, rem, lane);
+      wait_loads_and_barrier<0>();
     }
   }
 
@@ -390,48 +473,86 @@ attn_kernel(AttnArgs a) {
         }
       }
     }
+    // the counted waits of phase L must see tile loads only
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 
   // =========================== phase L =====================================
+  // The 32 rows of a W1 / W2 block are read in "quad-swapped" order (lane r takes
+  // block row sigma(r), sigma exchanging bits 2 and 3 of r), so that the
+  // accumulator of one product is, register for register, the B operand of the
+  // next one in natural k order and no operand needs a permuted copy in memory.
   float nL[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) nL[qb] = 0.f;
-  if (cr.l_hi > 0) {
-    const bf16_t* W1 = a.w1_q + (int64_t)h * HID * D;
-    const bf16_t* W2 = a.w2_q + (int64_t)h * DP * HID;
-    const bf16_t* St = a.state_s + ((int64_t)bh * a.state_slots + tc) * (int64_t)D * DP;  // [D][DP]
-    const float* zt = a.state_z + ((int64_t)bh * a.state_slots + tc) * DP;
-    __syncthreads();  // all waves are done with the K/V tiles
-    for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_q[(int64_t)h * HID + i];
-    for (int i = tid; i < DP; i += NT) {
-      sb2[i] = a.b2_q[(int64_t)h * DP + i];
-      sz[i] = zt[i];
-    }
+  if (has_linear) {
+    using SCH = LinSched<D>;
+    constexpr int NW1 = HID / 64, NPB = DP / 32;
+    const char* W1 = reinterpret_cast<const char*>(a.w1_q + (int64_t)h * HID * D);
+    const char* W2 = reinterpret_cast<const char*>(a.w2_q + (int64_t)h * DP * HID);
+    const char* St = reinterpret_cast<const char*>(a.state_s + ((int64_t)bh * a.state_slots + tc) * (int64_t)D * DP);
+
+    auto issue_tile = [&](auto KIND, int idx, char* dst) {
+      constexpr int kind = decltype(KIND)::value;
+      if constexpr (kind == kW1) {
+        tile_load_direct<2 * D, TB>(W1 + idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
+      } else if constexpr (kind == kW2) {
+        tile_load_direct<2 * D, TB>(W2 + idx * 32 * (4 * D), dst, wave, lane,
+                                    [](int R) { return (R & 31) * (4 * D) + (R >> 5) * (2 * D); });
+      } else {
+        tile_load_direct<128, TB>(St + idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
+      }
+    };
+    auto buf = [&](auto I) -> char* {
+      constexpr int i = decltype(I)::value;
+      if constexpr (i == 0) return A0;
+      else if constexpr (i == 1) return A1;
+      else if constexpr (i == 2) return A2;
+      else return A3;
+    };
+    auto issue_all = [&](auto SD) {   // the tiles a step (or the prologue) issues
+      constexpr LinStep sd = decltype(SD)::value;
+      if constexpr (sd.n_issue > 0)
+        issue_tile(std::integral_constant<int, sd.kind[0]>{}, sd.idx[0], buf(std::integral_constant<int, sd.buf[0]>{}));
+      if constexpr (sd.n_issue > 1)
+        issue_tile(std::integral_constant<int, sd.kind[1]>{}, sd.idx[1], buf(std::integral_constant<int, sd.buf[1]>{}));
+    };
+    // all K/V tiles are dead: the softmax loop ended with a barrier
+    static_for<SCH::NPRO>([&](auto I) {
+      issue_all(LinProC<D, decltype(I)::value>{});
+    });
+
     // with c = 0 the linear terms carry exp(-m) relative to the softmax terms
     float lin_scale[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
       lin_scale[qb] = (a.stab_mode == 1) ? __builtin_amdgcn_exp2f(-mrun[qb]) : 1.f;
 
-    // ---- U^T = relu(W1 Q^T + b1), kept as bf16 B operands -------------------
-    bf16x8 Ub[QB][HID / 16];
-    {
-      TileRegs<64, D, NT> wreg;
-      tile_load<64, D, NT, false>(wreg, W1, D, 64, tid);
-      constexpr int NSLAB = HID / 64;
+    // per-lane byte offsets inside a W tile: block row sigma(r), k-step ks
+    const int sr = (r & 0x13) | ((r & 4) << 1) | ((r & 8) >> 1);
+    int woff[KS];
 #pragma unroll
-      for (int sl = 0; sl < NSLAB; ++sl) {
-        __syncthreads();
-        tile_store<64, D, NT, false>(wreg, bufA, C::LDK, tid);
-        __syncthreads();
-        if (sl + 1 < NSLAB) tile_load<64, D, NT, false>(wreg, W1 + (int64_t)(sl + 1) * 64 * D, D, 64, tid);
+    for (int ks = 0; ks < KS; ++ks) woff[ks] = tile_off<2 * D>(sr, 16 * ks + 8 * g);
+    // accumulator register 4i+j of lane half g is block row 8i+4g+j, which after
+    // the row permutation is unit 16(i>>1) + 8g + 4(i&1) + j of the block
+    auto unit_of = [&](int i) { return 16 * (i >> 1) + 8 * g + 4 * (i & 1); };
+
+    bf16x8 Ub[QB][HID / 16];  // U^T = relu(W1 Q^T + b1) as B operands, natural k order
+    static_for<NW1 + NPB>([&](auto ST) {
+      constexpr int st = decltype(ST)::value;
+      constexpr LinStep sd = LinStepC<D, st>::value;
+      wait_loads_and_barrier<sd.younger * LPT>();
+      issue_all(LinStepC<D, st>{});
+      if constexpr (st < NW1) {
+        // ---- two 32-row blocks of hidden units ------------------------------------
+        const char* Ws = buf(std::integral_constant<int, sd.buf_w>{});
 #pragma unroll
         for (int hb2 = 0; hb2 < 2; ++hb2) {
-          const int hb = 2 * sl + hb2;  // 32-row block of hidden units
+          const int hb = 2 * st + hb2;
           f32x16 acc[QB];
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            f32x4 bias = *reinterpret_cast<const f32x4*>(sb1 + 32 * hb + 8 * i + 4 * g);
+            f32x4 bias = *reinterpret_cast<const f32x4*>(sb1 + 32 * hb + unit_of(i));
 #pragma unroll
             for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -439,7 +560,7 @@ attn_kernel(AttnArgs a) {
           }
 #pragma unroll
           for (int ks = 0; ks < KS; ++ks) {
-            bf16x8 wf = lds_read_frag(bufA + (32 * hb2 + r) * C::LDK + 16 * ks + 8 * g);
+            bf16x8 wf = *reinterpret_cast<const bf16x8*>(Ws + hb2 * (32 * 2 * D) + woff[ks]);
 #pragma unroll
             for (int qb = 0; qb < QB; ++qb) acc[qb] = mfma(wf, Qr[qb][ks], acc[qb]);
           }
@@ -451,32 +572,17 @@ attn_kernel(AttnArgs a) {
             Ub[qb][2 * hb + 1] = acc_to_operand(acc[qb], 1);
           }
         }
-      }
-    }
-
-    // ---- per 32 features: psi^T = relu(W2 U^T + b2), phi, read-out ----------
-    {
-      TileRegs<32, HID, NT> wreg;
-      TileRegs<D, 32, NT> sreg;
-      tile_load<32, HID, NT, false>(wreg, W2, HID, 32, tid);
-      tile_load<D, 32, NT, false>(sreg, St, DP, D, tid);
-      constexpr int NPB = DP / 32;
-#pragma unroll 1
-      for (int pb = 0; pb < NPB; ++pb) {
-        __syncthreads();
-        tile_store<32, HID, NT, true>(wreg, bufA, C::LDW2, tid);
-        tile_store<D, 32, NT, true>(sreg, bufB, C::LDS_S, tid);
-        __syncthreads();
-        if (pb + 1 < NPB) {
-          tile_load<32, HID, NT, false>(wreg, W2 + (int64_t)(pb + 1) * 32 * HID, HID, 32, tid);
-          tile_load<D, 32, NT, false>(sreg, St + (pb + 1) * 32, DP, D, tid);
-        }
+      } else {
+        // ---- 32 features: psi^T = relu(W2 U^T + b2), phi, read-out ------------------
+        const int pb = st - NW1;
+        const char* Ws = buf(std::integral_constant<int, sd.buf_w>{});
+        const char* Ss = buf(std::integral_constant<int, sd.buf_s>{});
         f32x16 acc[QB];
         float zv[16];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          f32x4 bias = *reinterpret_cast<const f32x4*>(sb2 + 32 * pb + 8 * i + 4 * g);
-          f32x4 zz = *reinterpret_cast<const f32x4*>(sz + 32 * pb + 8 * i + 4 * g);
+          f32x4 bias = *reinterpret_cast<const f32x4*>(sb2 + 32 * pb + unit_of(i));
+          f32x4 zz = *reinterpret_cast<const f32x4*>(sz + 32 * pb + unit_of(i));
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
 #pragma unroll
@@ -485,10 +591,13 @@ attn_kernel(AttnArgs a) {
           }
         }
 #pragma unroll
-        for (int ks = 0; ks < HID / 16; ++ks) {
-          bf16x8 wf = lds_read_frag(bufA + r * C::LDW2 + 16 * ks + 8 * g);
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll
-          for (int qb = 0; qb < QB; ++qb) acc[qb] = mfma(wf, Ub[qb][ks], acc[qb]);
+          for (int ks = 0; ks < KS; ++ks) {
+            bf16x8 wf = *reinterpret_cast<const bf16x8*>(Ws + half * (32 * 2 * D) + woff[ks]);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb) acc[qb] = mfma(wf, Ub[qb][half * KS + ks], acc[qb]);
+          }
         }
         const bool squared = (32 * pb >= DP / 2);
         bf16x8 Fb[QB][2];
@@ -507,17 +616,21 @@ attn_kernel(AttnArgs a) {
           Fb[qb][0] = acc_to_operand(acc[qb], 0);
           Fb[qb][1] = acc_to_operand(acc[qb], 1);
         }
+        // S tile: rows d, 64 columns = two feature blocks; this block's 32 columns
+        // start at 32(pb&1), k-step sidx of it is chunk 4(pb&1) + 2 sidx + g
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
+        for (int sidx = 0; sidx < 2; ++sidx) {
 #pragma unroll
           for (int db = 0; db < DB; ++db) {
-            bf16x8 sf = lds_read_frag(bufB + (32 * db + r) * C::LDS_S + 16 * s + 8 * g);
+            const int row = 32 * db + r;
+            const int c = (4 * (pb & 1) + 2 * sidx) | g;
+            bf16x8 sf = *reinterpret_cast<const bf16x8*>(Ss + row * 128 + ((c ^ swz<128>(row)) << 4));
 #pragma unroll
-            for (int qb = 0; qb < QB; ++qb) O[db][qb] = mfma(sf, Fb[qb][s], O[db][qb]);
+            for (int qb = 0; qb < QB; ++qb) O[db][qb] = mfma(sf, Fb[qb][sidx], O[db][qb]);
           }
         }
       }
-    }
+    });
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb) nL[qb] = half_swap_sum(nL[qb]);
   }
@@ -565,7 +678,9 @@ static int attn_qb() {
 
 int attn_query_tile(int d) { return attn_qb() == 2 ? 256 : 128; }
 
-hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream) {
+hipError_t launch_attn(const AttnArgs& a0, int d, int grid, hipStream_t stream) {
+  AttnArgs a = a0;
+  { const char* e = getenv("REHYAT_EXP"); a.exp_flags = e ? atoi(e) : 0; }
   const int qb = attn_qb();
   if (d == 128 && qb == 1) {
     hipLaunchKernelGGL((attn_kernel<128, 1>), dim3(grid), dim3(256), 0, stream, a);
