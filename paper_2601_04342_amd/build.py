@@ -10,6 +10,9 @@ SOURCES = ["rehyat_api.hip", "rehyat_state.hip", "rehyat_prefix.hip", "rehyat_at
 HEADERS = ["rehyat_device.h", "rehyat_kernels.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+         # no NaN is ever produced on purpose (masked scores are -inf, never inf - inf):
+         # lets max() compile to one instruction instead of canonicalise + max
+         "-fno-honor-nans",
          # packed fp32 forms are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

@@ -177,6 +177,63 @@ __device__ __forceinline__ void tile_store(const TileRegs<ROWS, COLS, NT>& regs,
   }
 }
 
+// ---------------------------------------------------------------------------
+// LDS tiles are [rows][ROWBYTES] with unpadded rows, filled by direct
+// global->LDS loads (each wave instruction moves 1 KB to consecutive LDS
+// bytes, so rows cannot be padded).  Bank conflicts are avoided by permuting
+// the 16-byte chunks of a row: chunk c of row `row` is stored at chunk position
+// c ^ swz(row).  swz is a bijection of the rows that a 32x32x16 A-fragment read
+// touches together (16 consecutive rows, same chunk) onto chunk positions, and
+// it also separates the 4 consecutive rows that one transposing read touches.
+// ---------------------------------------------------------------------------
+template <int ROWBYTES>
+__device__ __forceinline__ int swz(int row) {
+  if (ROWBYTES == 256) return ((row & 3) << 2) | ((row >> 2) & 3);   // 16 chunks per row
+  return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);                  // 128-byte rows, 8 chunks
+}
+
+// byte offset of element (row, col) inside a tile whose rows hold ROWBYTES/2 bf16
+template <int ROWBYTES>
+__device__ __forceinline__ int tile_off(int row, int col) {
+  return row * ROWBYTES + ((((col >> 3) ^ swz<ROWBYTES>(row)) << 4) | ((col & 7) << 1));
+}
+
+// Direct loads of one tile.  Wave w of NW moves the 1 KB blocks w, w+NW, ...; lane i of
+// a block fills LDS chunk slot i, so it fetches the global chunk that the
+// swizzle assigns to that slot.  `rowaddr(R)` gives the byte offset, from
+// `gbase`, of the global row segment that becomes tile row R.
+template <int ROWBYTES, int TILE_BYTES, typename RowAddr, int NW = 4>
+__device__ __forceinline__ void tile_load_direct(const char* gbase, char* lds_tile, int wave, int lane,
+                                                 RowAddr rowaddr) {
+  constexpr int CPR = ROWBYTES / 16;     // chunks per row
+  constexpr int RPB = 1024 / ROWBYTES;   // rows per 1 KB block
+  constexpr int NBLK = TILE_BYTES / 1024;
+  static_assert(NBLK % NW == 0, "blocks of a tile are dealt evenly to the waves");
+#pragma unroll
+  for (int n = 0; n < NBLK / NW; ++n) {
+    const int blk = wave + NW * n;
+    const int R = blk * RPB + lane / CPR;
+    const int c = (lane % CPR) ^ swz<ROWBYTES>(R);
+    const char* src = gbase + (uint32_t)(rowaddr(R) + c * 16);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(lds_tile + blk * 1024), 16, 0, 0);
+  }
+}
+
+// Wait until at most N of this wave's direct loads are outstanding (and all of
+// its LDS accesses are done), then workgroup barrier.  Written as one asm block:
+// the compiler's own barrier would wait for every outstanding direct load and
+// so serialise the prefetch with the computation.
+template <int N>
+__device__ __forceinline__ void wait_loads_and_barrier() {
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ bf16x8 join_tr(i16x4 lo, i16x4 hi) {
+  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short i16x8;
+  i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
+
 // Combine a per-lane value across the two 32-lane halves of the wave with
 // v_permlane32_swap: it exchanges the high half of its first register with the
 // low half of its second, so starting from two copies of x one register ends

@@ -5,35 +5,41 @@
 // second half of the output squared) evaluated on the fly from K -- phi_k(K)
 // never goes to HBM.
 //
-// One workgroup = 4 waves walks its token range in tiles of 64 tokens.  Wave w
-// owns hidden units and output features [w*D/2, (w+1)*D/2): it produces that
-// slice of U = relu(K W1^T + b1) for the tile (W1 resident in LDS), the four
-// waves exchange U through LDS, then each wave forms its feature slice
-// psi = relu(U W2^T + b2) with its W2 rows resident in registers, squares the
-// upper half, and accumulates V^T phi into its d x D/2 slice of the state held
-// in MFMA accumulators for the whole token range.
+// One workgroup of NW waves walks its token range in tiles of 64 tokens.  Wave
+// w owns hidden units and output features [32w, 32w+32): it produces that slice
+// of U = relu(K W1^T + b1) for the tile (W1 resident in LDS), the waves
+// exchange U through LDS, then each wave forms its feature slice
+// psi = relu(U W2^T + b2) with its W2 rows resident in registers, squares it if
+// it lies in the upper half, and accumulates V^T phi into its d x 32 slice of
+// the state, held in MFMA accumulators for the whole token range.
+//
+// K and V tiles arrive by direct global->LDS loads (chunk-swizzled rows, see
+// tile_load_direct), each issued half a tile step ahead of its first use: the
+// K tile of step t+1 once every wave is past the first half of step t, the V
+// tile of step t+1 once step t is complete.
+#include <type_traits>
+
 #include "rehyat_device.h"
 #include "rehyat_kernels.h"
 
 namespace rehyat {
 
-template <int D>
-__global__ void __launch_bounds__(256)
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW)
 state_kernel(StateArgs a) {
   constexpr int HID = 2 * D, DP = 2 * D;
   constexpr int KS = D / 16;      // k-steps across the head dimension
   constexpr int KS2 = HID / 16;   // k-steps across the hidden layer
   constexpr int DB = D / 32;      // 32-row blocks of the head dimension
-  constexpr int SL = DP / 4;      // features (and hidden units) per wave
-  constexpr int CB = SL / 32;     // 32-wide blocks in a wave's slice
-  constexpr int NT = 256;
-  constexpr int LDX = D + 8;      // row stride of the K, V and W1 tiles
-  constexpr int LDU = HID + 8;    // row stride of the U tile
+  constexpr int NT = 64 * NW;
+  constexpr int TB = 64 * 2 * D;  // bytes of a K, V or W1 tile (64 rows of 2D bytes)
+  constexpr int UROW = HID * 2;   // bytes of a row of U
+  static_assert(DP / NW == 32, "each wave owns 32 features");
 
-  __shared__ __attribute__((aligned(16))) bf16_t W1s[HID * LDX];
-  __shared__ __attribute__((aligned(16))) bf16_t Xs[64 * LDX];
-  __shared__ __attribute__((aligned(16))) bf16_t Vs[64 * LDX];
-  __shared__ __attribute__((aligned(16))) bf16_t Us[64 * LDU];
+  __shared__ __attribute__((aligned(1024))) char W1s[(HID / 64) * TB];
+  __shared__ __attribute__((aligned(1024))) char Xs[TB];
+  __shared__ __attribute__((aligned(1024))) char Vs[TB];
+  __shared__ __attribute__((aligned(1024))) char Us[64 * UROW];
   __shared__ __attribute__((aligned(16))) float sb1[HID];
 
   const int tid = threadIdx.x;
@@ -41,6 +47,7 @@ state_kernel(StateArgs a) {
   const int wave = tid >> 6;
   const int g = lane >> 5;
   const int r = lane & 31;
+  const int i16 = lane & 15;
 
   const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);
   if (item >= a.n_items) return;
@@ -59,169 +66,171 @@ state_kernel(StateArgs a) {
   const int64_t len = seg_hi - seg_lo;
   const int64_t lo = seg_lo + (len * sp) / a.nsplit;
   const int64_t hi = seg_lo + (len * (sp + 1)) / a.nsplit;
+  const int n_full = (int)((hi - lo) / 64);
+  const int rem = (int)((hi - lo) - 64 * (int64_t)n_full);
 
-  const bf16_t* Kg = a.k + (int64_t)bh * N * D;
-  const bf16_t* Vg = a.v + (int64_t)bh * N * D;
-  const bf16_t* W1 = a.w1_k + (int64_t)h * HID * D;
+  const char* Kb = reinterpret_cast<const char*>(a.k + ((int64_t)bh * N + lo) * D);
+  const char* Vb = reinterpret_cast<const char*>(a.v + ((int64_t)bh * N + lo) * D);
+  const char* W1 = reinterpret_cast<const char*>(a.w1_k + (int64_t)h * HID * D);
   const bf16_t* W2 = a.w2_k + (int64_t)h * DP * HID;
 
   // ---- resident operands ----------------------------------------------------
-  {
-    // W1 [HID][D] -> LDS, 64 rows at a time
-#pragma unroll
-    for (int sl = 0; sl < HID / 64; ++sl) {
-      TileRegs<64, D, NT> w;
-      tile_load<64, D, NT, false>(w, W1 + (int64_t)sl * 64 * D, D, 64, tid);
-      tile_store<64, D, NT, false>(w, W1s + sl * 64 * LDX, LDX, tid);
-    }
-    for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_k[(int64_t)h * HID + i];
-  }
+  for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_k[(int64_t)h * HID + i];
+  const int unit = wave * 32 + r;  // this lane's feature (a column of the wave's products)
+  const float b2v = a.b2_k[(int64_t)h * DP + unit];
   // W2 rows of this wave's features as B operands: column = feature, k = hidden
-  bf16x8 w2f[CB][KS2];
-  float b2v[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) {
-    const int unit = wave * SL + 32 * cb + r;
+  bf16x8 w2f[KS2];
+  {
     const bf16_t* p = W2 + (int64_t)unit * HID + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < KS2; ++ks) w2f[cb][ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
-    b2v[cb] = a.b2_k[(int64_t)h * DP + unit];
+    for (int ks = 0; ks < KS2; ++ks) w2f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
+  auto contiguous = [](int R) { return R * (2 * D); };
+  // tile `it` of K or V, rows at or beyond `valid` re-read the last valid row
+  auto issue_tile = [&](const char* gb, char* dst, int it, int valid) {
+    const char* src = gb + (int64_t)it * TB;
+    if (valid >= 64) {
+      tile_load_direct<2 * D, TB, decltype(contiguous), NW>(src, dst, wave, lane, contiguous);
+    } else {
+      auto clamped = [valid](int R) { return (R < valid ? R : valid - 1) * (2 * D); };
+      tile_load_direct<2 * D, TB, decltype(clamped), NW>(src, dst, wave, lane, clamped);
+    }
+  };
+  const int n_tiles = n_full + (rem > 0 ? 1 : 0);
+  auto valid_of = [&](int it) { return it < n_full ? 64 : rem; };
+#pragma unroll
+  for (int j = 0; j < HID / 64; ++j)
+    tile_load_direct<2 * D, TB, decltype(contiguous), NW>(W1 + j * TB, W1s + j * TB, wave, lane, contiguous);
+  if (n_tiles > 0) {
+    issue_tile(Kb, Xs, 0, valid_of(0));
+    issue_tile(Vb, Vs, 0, valid_of(0));
   }
 
-  // state slice: acc[db][cb] register 4i+j = (row d = 32db+8i+4g+j, feature wave*SL+32cb+r)
-  f32x16 acc[DB][CB];
+  // ---- per-lane LDS byte offsets ----------------------------------------------
+  const int hrow = wave * 32 + r;                      // W1 row of this lane's A fragment
+  int w1off[KS], xoff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    w1off[ks] = (hrow >> 6) * TB + tile_off<2 * D>(hrow & 63, 16 * ks + 8 * g);
+    xoff[ks] = tile_off<2 * D>(r, 16 * ks + 8 * g);    // + 32 rows for the second token block
+  }
+  // U[token][hidden], rows of UROW bytes, 16-byte chunks swizzled by swz<256>(token)
+  int uwoff[4];                                        // write: token r, units 32w + 8i + 4g .. +3
+#pragma unroll
+  for (int i = 0; i < 4; ++i) uwoff[i] = r * UROW + (((wave * 4 + i) ^ swz<256>(r)) << 4) + 8 * g;
+  int uroff[KS2];                                      // read: A fragment, token r, k-step ks2
+#pragma unroll
+  for (int ks = 0; ks < KS2; ++ks) uroff[ks] = r * UROW + (((2 * ks + g) ^ swz<256>(r)) << 4);
+  int voff_lo[DB], voff_hi[DB];                        // transposing reads of V, see softmax kernel
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    const int col = 32 * db + 16 * (r >> 4) + 4 * (i16 & 3);
+    voff_lo[db] = tile_off<2 * D>(4 * g + (i16 >> 2), col);
+    voff_hi[db] = tile_off<2 * D>(8 + 4 * g + (i16 >> 2), col);
+  }
+
+  // state slice: acc[db] register 4i+j = (row d = 32db+8i+4g+j, feature 32w+r)
+  f32x16 acc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[db][cb][e] = 0.f;
-  float zacc[CB];
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) zacc[cb] = 0.f;
+    for (int e = 0; e < 16; ++e) acc[db][e] = 0.f;
+  float zacc = 0.f;
+  const bool squared = (wave * 32 >= DP / 2);
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  TileRegs<64, D, NT> kreg, vreg;
-  if (lo < hi) {
-    int valid = (int)((hi - lo) < 64 ? (hi - lo) : 64);
-    tile_load<64, D, NT, true>(kreg, Kg + lo * D, D, valid, tid);
-    tile_load<64, D, NT, true>(vreg, Vg + lo * D, D, valid, tid);
-  }
-  for (int64_t t0 = lo; t0 < hi; t0 += 64) {
-    __syncthreads();  // previous tile consumed (also orders the W1 / bias staging)
-    tile_store<64, D, NT, false>(kreg, Xs, LDX, tid);
-    tile_store<64, D, NT, false>(vreg, Vs, LDX, tid);
-    __syncthreads();
-    if (t0 + 64 < hi) {
-      int64_t rem = hi - (t0 + 64);
-      int valid = (int)(rem < 64 ? rem : 64);
-      tile_load<64, D, NT, true>(kreg, Kg + (t0 + 64) * D, D, valid, tid);
-      tile_load<64, D, NT, true>(vreg, Vg + (t0 + 64) * D, D, valid, tid);
-    }
-    // ---- U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden]
+  wait_loads_and_barrier<0>();   // W1, first K and V tiles, bias vector
+
+  auto tile_step = [&](auto TAILC, int it) {
+    constexpr bool TAIL = decltype(TAILC)::value;
+    // ---- first half: U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden]
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
+      f32x16 u;
 #pragma unroll
-      for (int rb = 0; rb < CB; ++rb) {
-        const int hrow = wave * SL + 32 * rb;  // first hidden unit of the block
-        f32x16 u;
+      for (int i = 0; i < 4; ++i) {
+        f32x4 bias = *reinterpret_cast<const f32x4*>(sb1 + wave * 32 + 8 * i + 4 * g);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          f32x4 bias = *reinterpret_cast<const f32x4*>(sb1 + hrow + 8 * i + 4 * g);
+        for (int j = 0; j < 4; ++j) u[4 * i + j] = bias[j];
+      }
 #pragma unroll
-          for (int j = 0; j < 4; ++j) u[4 * i + j] = bias[j];
-        }
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 wf = *reinterpret_cast<const bf16x8*>(W1s + w1off[ks]);
+        bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + xoff[ks] + tb * (32 * 2 * D));
+        u = mfma(wf, xf, u);
+      }
+      // register 4i+j = (hidden 32w+8i+4g+j, token 32tb+r)
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          bf16x8 wf = lds_read_frag(W1s + (hrow + r) * LDX + 16 * ks + 8 * g);
-          bf16x8 xf = lds_read_frag(Xs + (32 * tb + r) * LDX + 16 * ks + 8 * g);
-          u = mfma(wf, xf, u);
-        }
-        // register 4i+j = (hidden hrow+8i+4g+j, token 32tb+r)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          u32x2 pk;
-          pk[0] = pack_bf16(fmaxf(u[4 * i], 0.f), fmaxf(u[4 * i + 1], 0.f));
-          pk[1] = pack_bf16(fmaxf(u[4 * i + 2], 0.f), fmaxf(u[4 * i + 3], 0.f));
-          *reinterpret_cast<u32x2*>(Us + (32 * tb + r) * LDU + hrow + 8 * i + 4 * g) = pk;
-        }
+      for (int i = 0; i < 4; ++i) {
+        u32x2 pk;
+        pk[0] = pack_bf16(fmaxf(u[4 * i], 0.f), fmaxf(u[4 * i + 1], 0.f));
+        pk[1] = pack_bf16(fmaxf(u[4 * i + 2], 0.f), fmaxf(u[4 * i + 3], 0.f));
+        *reinterpret_cast<u32x2*>(Us + uwoff[i] + tb * (32 * UROW)) = pk;
       }
     }
-    __syncthreads();  // U complete
-    const bool tail = (t0 + 64 > hi);
+    wait_loads_and_barrier<0>();   // U complete; this tile's V has landed; X is free
+    if (it + 1 < n_tiles) issue_tile(Kb, Xs, it + 1, valid_of(it + 1));
+    // ---- second half ---------------------------------------------------------------
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
-      // ---- psi slice = relu(U W2[slice]^T + b2): rows = tokens, columns = features
-      f32x16 ps[CB];
-#pragma unroll
-      for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) ps[cb][e] = 0.f;
+      // psi slice = relu(U W2[slice]^T + b2): rows = tokens, columns = features
+      f32x16 ps = zero;
 #pragma unroll
       for (int ks = 0; ks < KS2; ++ks) {
-        bf16x8 uf = lds_read_frag(Us + (32 * tb + r) * LDU + 16 * ks + 8 * g);
-#pragma unroll
-        for (int cb = 0; cb < CB; ++cb) ps[cb] = mfma(uf, w2f[cb][ks], ps[cb]);
+        bf16x8 uf = *reinterpret_cast<const bf16x8*>(Us + uroff[ks] + tb * (32 * UROW));
+        ps = mfma(uf, w2f[ks], ps);
       }
-      bf16x8 fb[CB][2];
+      float part = 0.f;
 #pragma unroll
-      for (int cb = 0; cb < CB; ++cb) {
-        const bool squared = (wave * SL + 32 * cb >= DP / 2);
-        float part = 0.f;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          float x = fmaxf(ps[cb][e] + b2v[cb], 0.f);
-          if (squared) x = x * x;
-          if (tail) {
-            int64_t tok = t0 + 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
-            if (tok >= hi) x = 0.f;
-          }
-          x = bf16_round(x);
-          ps[cb][e] = x;
-          part += x;
+      for (int e = 0; e < 16; ++e) {
+        float x = fmaxf(ps[e] + b2v, 0.f);
+        if (squared) x = x * x;
+        if (TAIL) {
+          if (32 * tb + 8 * (e >> 2) + 4 * g + (e & 3) >= rem) x = 0.f;   // token beyond the range
         }
-        zacc[cb] += part;
-        fb[cb][0] = acc_to_operand(ps[cb], 0);
-        fb[cb][1] = acc_to_operand(ps[cb], 1);
+        x = bf16_round(x);
+        ps[e] = x;
+        part += x;
       }
-      // ---- state slice += V^T phi
+      zacc += part;
+      // state slice += V^T phi, two 16-token steps
 #pragma unroll
       for (int s = 0; s < 2; ++s) {
+        bf16x8 fb = acc_to_operand(ps, s);
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          bf16x8 vf = lds_read_frag_transposed(Vs, LDX, 32 * tb + 16 * s, 32 * db, lane);
-#pragma unroll
-          for (int cb = 0; cb < CB; ++cb) acc[db][cb] = mfma(vf, fb[cb][s], acc[db][cb]);
+          const int so = (2 * tb + s) * (16 * 2 * D);
+          i16x4 vlo = lds_read_tr(reinterpret_cast<const bf16_t*>(Vs + voff_lo[db] + so));
+          i16x4 vhi = lds_read_tr(reinterpret_cast<const bf16_t*>(Vs + voff_hi[db] + so));
+          acc[db] = mfma(join_tr(vlo, vhi), fb, acc[db]);
         }
       }
     }
-  }
+    wait_loads_and_barrier<0>();   // next K tile has landed; U and V are free
+    if (it + 1 < n_tiles) issue_tile(Vb, Vs, it + 1, valid_of(it + 1));
+  };
+
+  for (int it = 0; it < n_full; ++it) tile_step(std::false_type{}, it);
+  if (rem > 0) tile_step(std::true_type{}, n_full);
 
   // ---- write the partial: S^T [d][DP] fp32, then z [DP] ---------------------------
   float* P = a.partial + ((int64_t)bh * a.partial_slots + (int64_t)seg * a.nsplit + sp) * (int64_t)(D * DP + DP);
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int cb = 0; cb < CB; ++cb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int row = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);
-        P[row * DP + wave * SL + 32 * cb + r] = acc[db][cb][e];
-      }
-#pragma unroll
-  for (int cb = 0; cb < CB; ++cb) {
-    float ztot = zacc[cb] + __shfl_xor(zacc[cb], 32);
-    if (g == 0) P[D * DP + wave * SL + 32 * cb + r] = ztot;
-  }
+    for (int e = 0; e < 16; ++e) {
+      const int row = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);
+      P[row * DP + unit] = acc[db][e];
+    }
+  const float ztot = half_swap_sum(zacc);
+  if (g == 0) P[D * DP + unit] = ztot;
 }
-
-template __global__ void state_kernel<64>(StateArgs);
-template __global__ void state_kernel<128>(StateArgs);
 
 hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream) {
   if (d == 128) {
-    hipLaunchKernelGGL(state_kernel<128>, dim3(grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((state_kernel<128, 8>), dim3(grid), dim3(512), 0, stream, a);
   } else {
-    hipLaunchKernelGGL(state_kernel<64>, dim3(grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((state_kernel<64, 4>), dim3(grid), dim3(256), 0, stream, a);
   }
   return hipGetLastError();
 }
