@@ -20,7 +20,6 @@
 // All operands that are shared by the four waves (K and V tiles, then W1, W2
 // and the chunk state) travel global -> LDS with direct loads into four LDS
 // tile buffers, issued one or more steps ahead of their use.
-#include <cstdlib>
 #include <type_traits>
 #include <utility>
 
@@ -29,12 +28,10 @@
 
 namespace rehyat {
 
-// query blocks of 32 per wave: 1 -> 128-query workgroups, two resident per CU;
-// 2 -> 256-query workgroups, one per CU
-#ifndef REHYAT_ATTN_QB
-#define REHYAT_ATTN_QB 1
-#endif
-constexpr int kAttnQB = REHYAT_ATTN_QB;
+// Query blocks of 32 per wave.  1 -> 128-query workgroups, two resident per CU, whose
+// waves share each SIMD and fill each other's stalls; 2 (256-query workgroups, one per
+// CU, half the LDS operand traffic per MFMA) measured 30 % slower at the 480p shape.
+constexpr int kAttnQB = 1;
 
 template <int D, int QB>
 struct AttnShape {
@@ -299,18 +296,7 @@ attn_kernel(AttnArgs a) {
   const bf16_t* Kg = a.k + (int64_t)bh * N * D;
   const bf16_t* Vg = a.v + (int64_t)bh * N * D;
   bf16_t* Og = a.out + (int64_t)bh * N * D;
-  const bool has_linear = cr.l_hi > 0 && !(a.exp_flags & 2);
-
-  // ---- per-head vectors of phase L go to LDS first: their loads must be older
-  // than every direct load so that the counted waits below see only tile loads
-  if (has_linear) {
-    const float* zt = a.state_z + ((int64_t)bh * a.state_slots + tc) * DP;
-    for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_q[(int64_t)h * HID + i];
-    for (int i = tid; i < DP; i += NT) {
-      sb2[i] = a.b2_q[(int64_t)h * DP + i];
-      sz[i] = zt[i];
-    }
-  }
+  const bool has_linear = cr.l_hi > 0;
 
   // ---- queries of this wave, held as B operands ---------------------------
   const int64_t qw0 = q0 + wave * C::QW;
@@ -346,7 +332,7 @@ attn_kernel(AttnArgs a) {
   {
     const FragOffsets<D> fo = make_frag_offsets<D>(lane);
     const int64_t s_lo = cr.s_lo, s_hi = cr.s_hi;
-    const int n_full = (a.exp_flags & 1) ? 1 : (int)((s_hi - s_lo) / 64);
+    const int n_full = (int)((s_hi - s_lo) / 64);
     const int rem = (int)((s_hi - s_lo) - 64 * (int64_t)((s_hi - s_lo) / 64));  // keys in the ragged last tile
     const char* const Kb = reinterpret_cast<const char*>(Kg + s_lo * D);
     const char* const Vb = reinterpret_cast<const char*>(Vg + s_lo * D);
@@ -354,10 +340,20 @@ attn_kernel(AttnArgs a) {
     // K and V of tile `it` into the given buffers
     auto issue_kv = [&](int it, char* kd, char* vd) {
       const int64_t goff = (int64_t)it * TB;
-      tile_load_direct<2 * D, TB>(Kb + goff, kd, wave, lane, contiguous);
-      tile_load_direct<2 * D, TB>(Vb + goff, vd, wave, lane, contiguous);
+      tile_load_direct<2 * D, TB, 4>(Kb + goff, kd, wave, lane, contiguous);
+      tile_load_direct<2 * D, TB, 4>(Vb + goff, vd, wave, lane, contiguous);
     };
     if (n_full > 0) issue_kv(0, A0, A2);
+      // per-head vectors of phase L (their loads complete long before phase L, whose
+      // counted waits must see tile loads only)
+    if (has_linear) {
+      const float* zt = a.state_z + ((int64_t)bh * a.state_slots + tc) * DP;
+      for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_q[(int64_t)h * HID + i];
+      for (int i = tid; i < DP; i += NT) {
+        sb2[i] = a.b2_q[(int64_t)h * DP + i];
+        sz[i] = zt[i];
+      }
+    }
     wait_loads_and_barrier<0>();   // also publishes the bias vectors
     // Two tiles per trip so that buffer choice is static.  The loads of tile
     // it+1 go into the other buffer pair, whose last readers (tile it-1) all
@@ -379,8 +375,8 @@ attn_kernel(AttnArgs a) {
       // values) and their keys are masked
       const int64_t goff = (int64_t)((s_hi - s_lo) / 64) * TB;
       auto clamped = [rem](int R) { return (R < rem ? R : rem - 1) * (2 * D); };
-      tile_load_direct<2 * D, TB>(Kb + goff, A0, wave, lane, clamped);
-      tile_load_direct<2 * D, TB>(Vb + goff, A2, wave, lane, clamped);
+      tile_load_direct<2 * D, TB, 4>(Kb + goff, A0, wave, lane, clamped);
+      tile_load_direct<2 * D, TB, 4>(Vb + goff, A2, wave, lane, clamped);
       wait_loads_and_barrier<0>();
       softmax_tile<D, QB, true>(A0, A2, fo, Qr, O, mrun, lrun, sc, rem, lane);
       wait_loads_and_barrier<0>();
@@ -439,12 +435,12 @@ attn_kernel(AttnArgs a) {
     auto issue_tile = [&](auto KIND, int idx, char* dst) {
       constexpr int kind = decltype(KIND)::value;
       if constexpr (kind == kW1) {
-        tile_load_direct<2 * D, TB>(W1 + idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
+        tile_load_direct<2 * D, TB, 4>(W1 + idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
       } else if constexpr (kind == kW2) {
-        tile_load_direct<2 * D, TB>(W2 + idx * 32 * (4 * D), dst, wave, lane,
+        tile_load_direct<2 * D, TB, 4>(W2 + idx * 32 * (4 * D), dst, wave, lane,
                                     [](int R) { return (R & 31) * (4 * D) + (R >> 5) * (2 * D); });
       } else {
-        tile_load_direct<128, TB>(St + idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
+        tile_load_direct<128, TB, 4>(St + idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
       }
     };
     auto buf = [&](auto I) -> char* {
@@ -608,32 +604,13 @@ attn_kernel(AttnArgs a) {
   }
 }
 
-// Queries per workgroup: 128 (one 32-query block per wave, two workgroups per
-// CU) or 256 (two blocks per wave, one workgroup per CU).  REHYAT_ATTN_QB=1|2
-// in the environment overrides the default; read once.
-static int attn_qb() {
-  static int qb = [] {
-    const char* e = getenv("REHYAT_ATTN_QB");
-    int v = e ? atoi(e) : kAttnQB;
-    return (v == 2) ? 2 : 1;
-  }();
-  return qb;
-}
+int attn_query_tile(int d) { return AttnShape<128, kAttnQB>::QT; }
 
-int attn_query_tile(int d) { return attn_qb() == 2 ? 256 : 128; }
-
-hipError_t launch_attn(const AttnArgs& a0, int d, int grid, hipStream_t stream) {
-  AttnArgs a = a0;
-  { const char* e = getenv("REHYAT_EXP"); a.exp_flags = e ? atoi(e) : 0; }
-  const int qb = attn_qb();
-  if (d == 128 && qb == 1) {
-    hipLaunchKernelGGL((attn_kernel<128, 1>), dim3(grid), dim3(256), 0, stream, a);
-  } else if (d == 128) {
-    hipLaunchKernelGGL((attn_kernel<128, 2>), dim3(grid), dim3(256), 0, stream, a);
-  } else if (qb == 1) {
-    hipLaunchKernelGGL((attn_kernel<64, 1>), dim3(grid), dim3(256), 0, stream, a);
+hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream) {
+  if (d == 128) {
+    hipLaunchKernelGGL((attn_kernel<128, kAttnQB>), dim3(grid), dim3(256), 0, stream, a);
   } else {
-    hipLaunchKernelGGL((attn_kernel<64, 2>), dim3(grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((attn_kernel<64, kAttnQB>), dim3(grid), dim3(256), 0, stream, a);
   }
   return hipGetLastError();
 }

@@ -202,7 +202,7 @@ __device__ __forceinline__ int tile_off(int row, int col) {
 // a block fills LDS chunk slot i, so it fetches the global chunk that the
 // swizzle assigns to that slot.  `rowaddr(R)` gives the byte offset, from
 // `gbase`, of the global row segment that becomes tile row R.
-template <int ROWBYTES, int TILE_BYTES, typename RowAddr, int NW = 4>
+template <int ROWBYTES, int TILE_BYTES, int NW, typename RowAddr>
 __device__ __forceinline__ void tile_load_direct(const char* gbase, char* lds_tile, int wave, int lane,
                                                  RowAddr rowaddr) {
   constexpr int CPR = ROWBYTES / 16;     // chunks per row

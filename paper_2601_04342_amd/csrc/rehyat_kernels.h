@@ -63,7 +63,6 @@ struct AttnArgs {
   int state_slots;
   int stab_mode;
   int n_items, items_per_xcd;
-  int exp_flags;             // timing experiments only
 };
 
 // ---- transposes the carry into the [dprime][d] layout of the public state hook ----

@@ -90,17 +90,17 @@ state_kernel(StateArgs a) {
   auto issue_tile = [&](const char* gb, char* dst, int it, int valid) {
     const char* src = gb + (int64_t)it * TB;
     if (valid >= 64) {
-      tile_load_direct<2 * D, TB, decltype(contiguous), NW>(src, dst, wave, lane, contiguous);
+      tile_load_direct<2 * D, TB, NW>(src, dst, wave, lane, contiguous);
     } else {
       auto clamped = [valid](int R) { return (R < valid ? R : valid - 1) * (2 * D); };
-      tile_load_direct<2 * D, TB, decltype(clamped), NW>(src, dst, wave, lane, clamped);
+      tile_load_direct<2 * D, TB, NW>(src, dst, wave, lane, clamped);
     }
   };
   const int n_tiles = n_full + (rem > 0 ? 1 : 0);
   auto valid_of = [&](int it) { return it < n_full ? 64 : rem; };
 #pragma unroll
   for (int j = 0; j < HID / 64; ++j)
-    tile_load_direct<2 * D, TB, decltype(contiguous), NW>(W1 + j * TB, W1s + j * TB, wave, lane, contiguous);
+    tile_load_direct<2 * D, TB, NW>(W1 + j * TB, W1s + j * TB, wave, lane, contiguous);
   if (n_tiles > 0) {
     issue_tile(Kb, Xs, 0, valid_of(0));
     issue_tile(Vb, Vs, 0, valid_of(0));
