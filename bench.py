@@ -17,9 +17,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-# HBM bytes per launch of the fused attention kernel measured with rocprofv3
-# --pmc FETCH_SIZE / WRITE_SIZE (see profiles/); None until measured.
-ATTN_TRAFFIC_BYTES = None
+# HBM bytes per launch of the fused attention kernel on the wan480p workload, from
+# two rocprofv3 --pmc runs: 2.0 x FETCH_SIZE (172,961 KiB) + 1.0 x WRITE_SIZE
+# (98,280 KiB), the factors being those a 1 GiB device copy shows in the same runs
+# (profiles/wan480p_hbm_traffic_pmc.md).  Other workloads report null.
+ATTN_TRAFFIC_BYTES = {"wan480p": 454863744}
 
 
 def algorithmic_flops(w, overlap=0):
@@ -64,6 +66,10 @@ def main():
     ap.add_argument("--workload", default="wan480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=12)
+    ap.add_argument("--pmc-copy-mib", type=int, default=0,
+                    help="after the timed steps also run one plain device-to-device copy of this "
+                         "many MiB (a kernel of known HBM traffic that calibrates the FETCH_SIZE / "
+                         "WRITE_SIZE counters of a rocprofv3 --pmc run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (no sharding, no collectives); "
@@ -96,6 +102,13 @@ def main():
     prof = binding.profile_read()
     binding.profile_enable(False)
     assert torch.isfinite(out.float()).all()
+    if args.pmc_copy_mib > 0:
+        src = torch.full((args.pmc_copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     ms = dt * 1e3 / args.steps
     fl = algorithmic_flops(w)
@@ -118,9 +131,10 @@ def main():
         "kernel_ms": kern_ms,
         "kernel_launches_per_step": {kk: n / args.steps for kk, (_, n) in prof.items()},
         "workspace_bytes": binding.workspace_bytes(w.B, w.H, w.d),
-        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128>", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128, 1>", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": ATTN_TRAFFIC_BYTES},
+                     "frac": achieved / PEAK_BF16_TFLOPS,
+                     "traffic": ATTN_TRAFFIC_BYTES.get(w.name)},
         "state_kernel_tflops": (fl["state_kernel"] / (kern_ms["state"] * 1e-3) / 1e12
                                 if kern_ms["state"] else None),
     }
