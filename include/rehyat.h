@@ -140,6 +140,36 @@ int rehyat_forward_ex(const void *q, const void *k, const void *v,
                       void *stream);
 
 /*
+ * One step of the chunk-wise RNN (section 3.3, Eq. 14-18) for generation chunk by
+ * chunk: the caller owns the state and the K/V window, the library holds nothing
+ * between calls, and peak memory does not depend on how many chunks came before.
+ *
+ *   q_t           [B, H, n_q, d]    bf16 DEVICE  queries of the current chunk
+ *   k_win, v_win  [B, H, n_win, d]  bf16 DEVICE  the softmax window T^S_t of
+ *                 Eq. 12, oldest token first: the T_o overlap frames kept from
+ *                 earlier chunks, then the current chunk's own tokens
+ *   S [B, H, dprime, d] fp32, z [B, H, dprime] fp32  DEVICE, read and written:
+ *                 on entry the sums of Eq. 14-15 over every token older than the
+ *                 window (all zero before the first chunk); the read-out of
+ *                 Eq. 16 uses these values.  On return the first n_absorb
+ *                 tokens of the window have been added (Eq. 17-18): the tokens
+ *                 that are no longer inside the next chunk's window.
+ *   out_t         [B, H, n_q, d]    bf16 DEVICE  y of Eq. 5-9 for the chunk
+ *   n_absorb      0 <= n_absorb <= n_win
+ *   stab_mode     REHYAT_STAB_ROWMAX or REHYAT_STAB_NONE
+ *
+ * Feeding the chunks of a sequence in order, with the windows and n_absorb =
+ * s_lo(t+1) - s_lo(t) of rehyat_chunk_plan, gives the outputs of
+ * rehyat_forward_ex (same overlap) up to the rounding of a different summation
+ * split.  Asynchronous on `stream`; uses the workspace like a forward call.
+ * Supported: d in {64, 128}.
+ */
+int rehyat_step(const void *q_t, const void *k_win, const void *v_win,
+                const rehyat_phi_params *phi_params, float *S, float *z,
+                void *out_t, int B, int H, int d, int n_q, int n_win,
+                int n_absorb, int stab_mode, void *stream);
+
+/*
  * Running state of the chunk-wise RNN (Eq. 14-15, 17-18) after absorbing
  * tokens [0, upto) of every head, as the state kernels compute it:
  *   S_out [B, H, dprime, d] fp32,  z_out [B, H, dprime] fp32  (DEVICE)

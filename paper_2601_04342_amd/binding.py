@@ -19,7 +19,7 @@ STAB_ROWMAX, STAB_NONE = 0, 1
 
 # every symbol include/rehyat.h declares
 EXPORTS = ("rehyat_chunk_plan", "rehyat_workspace_bytes", "rehyat_set_workspace",
-           "rehyat_forward", "rehyat_forward_ex", "rehyat_state", "rehyat_shutdown",
+           "rehyat_forward", "rehyat_forward_ex", "rehyat_step", "rehyat_state", "rehyat_shutdown",
            "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error",
            "rehyat_profile_enable", "rehyat_profile_read")
 
@@ -71,6 +71,9 @@ def _load():
     lib.rehyat_forward_ex.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp,
                                       ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                       ctypes.POINTER(DebugOut), vp]
+    lib.rehyat_step.restype = ci
+    lib.rehyat_step.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp, vp, vp,
+                                ci, ci, ci, ci, ci, ci, ci, vp]
     lib.rehyat_state.restype = ci
     lib.rehyat_state.argtypes = [vp, vp, ctypes.POINTER(PhiParams), vp, vp,
                                  ci, ci, ci, ci, ci, ci, vp]
@@ -239,6 +242,36 @@ def forward(q, k, v, phi, T, HW, chunk, out=None, overlap=0, causal=True,
     if rc != OK:
         raise RehyatError(rc, "rehyat_forward_ex")
     return (out, comps) if debug else out
+
+
+def step(q_t, k_win, v_win, phi, S, z, n_absorb, out=None, stab_mode=STAB_ROWMAX, stream=None):
+    """One chunk of the chunk-wise RNN (Eq. 14-18).  q_t: CUDA bf16 [B, H, n_q, d];
+    k_win, v_win: [B, H, n_win, d], the softmax window oldest token first; S
+    [B, H, D', d] and z [B, H, D'] fp32 are read for the read-out and then
+    advanced in place by the first ``n_absorb`` window tokens.  Returns y_t."""
+    lib = _load()
+    for t in (q_t, k_win, v_win):
+        if t.dtype != torch.bfloat16 or not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise TypeError("q_t, k_win, v_win must be contiguous CUDA bf16 tensors [B, H, n, d]")
+    if k_win.shape != v_win.shape or k_win.shape[:2] != q_t.shape[:2] or k_win.shape[3] != q_t.shape[3]:
+        raise ValueError("q_t / k_win / v_win shapes are inconsistent")
+    B, H, n_q, d = q_t.shape
+    n_win = k_win.shape[2]
+    p, _ = _phi_struct(phi, d)
+    for t, shape in ((S, (B, H, p.dprime, d)), (z, (B, H, p.dprime))):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or tuple(t.shape) != shape:
+            raise TypeError(f"state tensors must be contiguous CUDA fp32 of shape {shape}")
+    if out is None:
+        out = torch.empty_like(q_t)
+    elif out.shape != q_t.shape or out.dtype != torch.bfloat16 or not out.is_contiguous():
+        raise TypeError("out must match q_t")
+    s = torch.cuda.current_stream() if stream is None else stream
+    rc = lib.rehyat_step(q_t.data_ptr(), k_win.data_ptr(), v_win.data_ptr(), ctypes.byref(p),
+                         S.data_ptr(), z.data_ptr(), out.data_ptr(), B, H, d, n_q, n_win,
+                         int(n_absorb), stab_mode, ctypes.c_void_p(s.cuda_stream))
+    if rc != OK:
+        raise RehyatError(rc, "rehyat_step")
+    return out
 
 
 def state(k, v, phi, T, HW, upto_frames, stream=None):

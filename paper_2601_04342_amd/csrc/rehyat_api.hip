@@ -169,6 +169,8 @@ int launch_state_window(const void* k, const void* v, const rehyat_phi_params* p
   s.partial_slots = kPartialSlots;
   s.n_items = B * H * n_seg * nsplit;
   s.items_per_xcd = (s.n_items + 7) / 8;
+  s.kv_bh_stride = (int64_t)T * HW * d;
+  s.step_n = 0;
   ProfScope prof(0, stream);
   hipError_t e = launch_state(s, d, s.items_per_xcd * 8, stream);
   if (e != hipSuccess) return hip_fail(e, "state kernel launch");
@@ -341,6 +343,8 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
     a.stab_mode = stab_mode;
     a.n_items = B * H * n_chunks * qtiles;
     a.items_per_xcd = (a.n_items + 7) / 8;
+    a.q_bh_stride = a.kv_bh_stride = (int64_t)T * HW * d;
+    a.step_nq = a.step_nwin = 0;
     hipError_t e;
     {
       ProfScope prof(2, st);
@@ -384,6 +388,120 @@ int rehyat_forward(const void* q, const void* k, const void* v, const rehyat_phi
                    void* out, int B, int H, int T, int HW, int d, int chunk, void* stream) {
   return rehyat_forward_ex(q, k, v, phi, out, B, H, T, HW, d, chunk, /*overlap=*/0, /*causal=*/1,
                            REHYAT_STAB_ROWMAX, nullptr, stream);
+}
+
+int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const rehyat_phi_params* phi,
+                float* S, float* z, void* out_t, int B, int H, int d, int n_q, int n_win,
+                int n_absorb, int stab_mode, void* stream) {
+  if (!q_t || !k_win || !v_win || !S || !z || !out_t) return REHYAT_E_NULL;
+  if (B < 1 || H < 1 || d < 1 || n_q < 1 || n_win < 1 || n_absorb < 0) return REHYAT_E_SHAPE;
+  if (n_absorb > n_win) return REHYAT_E_SHAPE;
+  if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
+  if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
+  int rc = check_phi(phi, d);
+  if (rc != REHYAT_OK) return rc;
+  if (stab_mode != REHYAT_STAB_ROWMAX && stab_mode != REHYAT_STAB_NONE) return REHYAT_E_SHAPE;
+  const int dp = phi->dprime;
+  hipStream_t st = (hipStream_t)stream;
+
+  std::lock_guard<std::mutex> lock(g_mu);
+  const WsLayout L = ws_layout(B, H, d, dp);
+  char* ws = nullptr;
+  rc = ensure_workspace(L.total, &ws);
+  if (rc != REHYAT_OK) return rc;
+
+  // caller's state -> carry
+  StateInArgs in;
+  in.S_in = S;
+  in.z_in = z;
+  in.carry = (float*)(ws + L.carry);
+  in.BH = B * H;
+  in.d = d;
+  in.dprime = dp;
+  hipError_t e = launch_state_in(in, st);
+  if (e != hipSuccess) return hip_fail(e, "state input kernel launch");
+
+  // increment of the tokens that leave the window, in pieces
+  int nsplit = 1;
+  if (n_absorb > 0) {
+    // one segment only: enough pieces to cover the chip, none shorter than a tile
+    nsplit = (2 * kCUs + B * H - 1) / (B * H);
+    if (nsplit > kPartialSlots) nsplit = kPartialSlots;
+    const int max_pieces = (n_absorb + 63) / 64;
+    if (nsplit > max_pieces) nsplit = max_pieces;
+    StateArgs s;
+    s.k = (const bf16_t*)k_win;
+    s.v = (const bf16_t*)v_win;
+    s.w1_k = (const bf16_t*)phi->w1_k;
+    s.b1_k = (const float*)phi->b1_k;
+    s.w2_k = (const bf16_t*)phi->w2_k;
+    s.b2_k = (const float*)phi->b2_k;
+    s.partial = (float*)(ws + L.partial);
+    s.H = H;
+    s.T = s.HW = s.chunk = 1;
+    s.overlap = 0;
+    s.chunk0 = 0;
+    s.n_seg = 1;
+    s.nsplit = nsplit;
+    s.partial_slots = kPartialSlots;
+    s.n_items = B * H * nsplit;
+    s.items_per_xcd = (s.n_items + 7) / 8;
+    s.kv_bh_stride = (int64_t)n_win * d;
+    s.step_n = n_absorb;
+    ProfScope prof(0, st);
+    e = launch_state(s, d, s.items_per_xcd * 8, st);
+    if (e != hipSuccess) return hip_fail(e, "state kernel launch");
+  }
+  // slot 0 <- state before the increment (what the read-out uses); carry += increment
+  rc = launch_prefix_window(ws, L, B, H, d, dp, /*n_chunks=*/1, /*n_seg=*/n_absorb > 0 ? 1 : 0, nsplit,
+                            /*first=*/false, st);
+  if (rc != REHYAT_OK) return rc;
+
+  AttnArgs a;
+  a.q = (const bf16_t*)q_t;
+  a.k = (const bf16_t*)k_win;
+  a.v = (const bf16_t*)v_win;
+  a.out = (bf16_t*)out_t;
+  a.w1_q = (const bf16_t*)phi->w1_q;
+  a.b1_q = (const float*)phi->b1_q;
+  a.w2_q = (const bf16_t*)phi->w2_q;
+  a.b2_q = (const float*)phi->b2_q;
+  a.state_s = (const bf16_t*)(ws + L.state_s);
+  a.state_z = (const float*)(ws + L.state_z);
+  a.dbg_m = a.dbg_nS = a.dbg_aS = a.dbg_nL = a.dbg_aL = nullptr;
+  a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)d));
+  a.H = H;
+  a.T = a.HW = a.chunk = 1;
+  a.overlap = 0;
+  a.chunk0 = 0;
+  a.n_win_chunks = 1;
+  const int qtile = attn_query_tile(d);
+  a.qtiles = (n_q + qtile - 1) / qtile;
+  a.state_slots = kStateSlots;
+  a.stab_mode = stab_mode;
+  a.n_items = B * H * a.qtiles;
+  a.items_per_xcd = (a.n_items + 7) / 8;
+  a.q_bh_stride = (int64_t)n_q * d;
+  a.kv_bh_stride = (int64_t)n_win * d;
+  a.step_nq = n_q;
+  a.step_nwin = n_win;
+  {
+    ProfScope prof(2, st);
+    e = launch_attn(a, d, a.items_per_xcd * 8, st);
+  }
+  if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
+
+  // carry -> caller's state
+  StateOutArgs o;
+  o.carry = (const float*)(ws + L.carry);
+  o.S_out = S;
+  o.z_out = z;
+  o.BH = B * H;
+  o.d = d;
+  o.dprime = dp;
+  e = launch_state_out(o, st);
+  if (e != hipSuccess) return hip_fail(e, "state output kernel launch");
+  return REHYAT_OK;
 }
 
 int rehyat_state(const void* k, const void* v, const rehyat_phi_params* phi, float* S_out,

@@ -288,14 +288,23 @@ attn_kernel(AttnArgs a) {
   const int bh = rest / a.n_win_chunks;
   const int t = a.chunk0 + tc;
   const int h = bh % a.H;
-  const ChunkRange cr = chunk_range(a.T, a.HW, a.chunk, a.overlap, t);
+  ChunkRange cr;
+  if (a.step_nq > 0) {  // streaming step: explicit ranges, state always read
+    cr.q_lo = 0;
+    cr.q_hi = a.step_nq;
+    cr.s_lo = 0;
+    cr.s_hi = a.step_nwin;
+    cr.l_hi = 1;
+  } else {
+    cr = chunk_range(a.T, a.HW, a.chunk, a.overlap, t);
+  }
   const int64_t q0 = cr.q_lo + (int64_t)qt * C::QT;
   if (q0 >= cr.q_hi) return;  // short last chunk: fewer query tiles
-  const int64_t N = (int64_t)a.T * a.HW;
-  const bf16_t* Qg = a.q + (int64_t)bh * N * D;
-  const bf16_t* Kg = a.k + (int64_t)bh * N * D;
-  const bf16_t* Vg = a.v + (int64_t)bh * N * D;
-  bf16_t* Og = a.out + (int64_t)bh * N * D;
+  const int64_t N = (int64_t)a.T * a.HW;  // rows per (b, h) of the debug outputs
+  const bf16_t* Qg = a.q + (int64_t)bh * a.q_bh_stride;
+  const bf16_t* Kg = a.k + (int64_t)bh * a.kv_bh_stride;
+  const bf16_t* Vg = a.v + (int64_t)bh * a.kv_bh_stride;
+  bf16_t* Og = a.out + (int64_t)bh * a.q_bh_stride;
   const bool has_linear = cr.l_hi > 0;
 
   // ---- queries of this wave, held as B operands ---------------------------

@@ -27,6 +27,9 @@ struct StateArgs {
   int partial_slots;    // slot stride per (b, h)
   int n_items;          // BH * n_seg * nsplit
   int items_per_xcd;
+  int64_t kv_bh_stride; // elements between the k (and v) rows of consecutive (b, h)
+  int step_n;           // > 0: one segment, rows [0, step_n) of k / v (streaming step); the
+                        // frame geometry above is then unused
 };
 
 // ---- prefix kernel: states S_t, z_t of the window's chunks ---------------------
@@ -63,6 +66,11 @@ struct AttnArgs {
   int state_slots;
   int stab_mode;
   int n_items, items_per_xcd;
+  int64_t q_bh_stride;   // elements between the q (and out) rows of consecutive (b, h)
+  int64_t kv_bh_stride;  // same for k and v
+  int step_nq, step_nwin;  // step_nq > 0 (streaming step): queries are rows [0, step_nq) of q,
+                           // the softmax window is rows [0, step_nwin) of k / v, the linear
+                           // state is slot 0; the frame geometry above is then unused
 };
 
 // ---- transposes the carry into the [dprime][d] layout of the public state hook ----
@@ -73,10 +81,19 @@ struct StateOutArgs {
   int BH, d, dprime;
 };
 
+// ---- caller's state [dprime][d] + z into the carry layout (inverse of StateOutArgs) ----
+struct StateInArgs {
+  const float* S_in;   // [BH, dprime, d]
+  const float* z_in;   // [BH, dprime]
+  float* carry;        // [BH, d*dprime + dprime]
+  int BH, d, dprime;
+};
+
 hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream);
 hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream);
 hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream);
 int attn_query_tile(int d);  // query tokens per workgroup of the attention kernel
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream);
+hipError_t launch_state_in(const StateInArgs& a, hipStream_t stream);
 
 }  // namespace rehyat

@@ -54,6 +54,19 @@ state_out_kernel(StateOutArgs a) {
   if (i < a.dprime) a.z_out[(int64_t)bh * a.dprime + i] = c[n + i];
 }
 
+__global__ void __launch_bounds__(256)
+state_in_kernel(StateInArgs a) {
+  const int bh = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;  // index into the carry's S^T [d][dprime]
+  const int n = a.d * a.dprime;
+  float* c = a.carry + (int64_t)bh * (n + a.dprime);
+  if (i < n) {
+    const int col = i / a.dprime, e = i % a.dprime;
+    c[i] = a.S_in[(int64_t)bh * n + (int64_t)e * a.d + col];
+  }
+  if (i < a.dprime) c[n + i] = a.z_in[(int64_t)bh * a.dprime + i];
+}
+
 hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream) {
   dim3 grid((a.elems / 4 + 255) / 256, a.BH);
   hipLaunchKernelGGL(prefix_kernel, grid, dim3(256), 0, stream, a);
@@ -63,6 +76,12 @@ hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream) {
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream) {
   dim3 grid((a.d * a.dprime + 255) / 256, a.BH);
   hipLaunchKernelGGL(state_out_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_state_in(const StateInArgs& a, hipStream_t stream) {
+  dim3 grid((a.d * a.dprime + 255) / 256, a.BH);
+  hipLaunchKernelGGL(state_in_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 

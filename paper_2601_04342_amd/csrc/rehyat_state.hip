@@ -56,21 +56,24 @@ state_kernel(StateArgs a) {
   const int seg = rest % a.n_seg;
   const int bh = rest / a.n_seg;
   const int h = bh % a.H;
-  const int64_t N = (int64_t)a.T * a.HW;
 
   // token range of this piece
-  const int tt = a.chunk0 + seg;
-  const int nchunks = num_chunks(a.T, a.chunk);
-  const int64_t seg_lo = chunk_range(a.T, a.HW, a.chunk, a.overlap, tt).s_lo;
-  const int64_t seg_hi = (tt + 1 < nchunks) ? chunk_range(a.T, a.HW, a.chunk, a.overlap, tt + 1).s_lo : N;
+  int64_t seg_lo = 0, seg_hi = a.step_n;
+  if (a.step_n <= 0) {
+    const int tt = a.chunk0 + seg;
+    const int nchunks = num_chunks(a.T, a.chunk);
+    seg_lo = chunk_range(a.T, a.HW, a.chunk, a.overlap, tt).s_lo;
+    seg_hi = (tt + 1 < nchunks) ? chunk_range(a.T, a.HW, a.chunk, a.overlap, tt + 1).s_lo
+                                : (int64_t)a.T * a.HW;
+  }
   const int64_t len = seg_hi - seg_lo;
   const int64_t lo = seg_lo + (len * sp) / a.nsplit;
   const int64_t hi = seg_lo + (len * (sp + 1)) / a.nsplit;
   const int n_full = (int)((hi - lo) / 64);
   const int rem = (int)((hi - lo) - 64 * (int64_t)n_full);
 
-  const char* Kb = reinterpret_cast<const char*>(a.k + ((int64_t)bh * N + lo) * D);
-  const char* Vb = reinterpret_cast<const char*>(a.v + ((int64_t)bh * N + lo) * D);
+  const char* Kb = reinterpret_cast<const char*>(a.k + (int64_t)bh * a.kv_bh_stride + lo * D);
+  const char* Vb = reinterpret_cast<const char*>(a.v + (int64_t)bh * a.kv_bh_stride + lo * D);
   const char* W1 = reinterpret_cast<const char*>(a.w1_k + (int64_t)h * HID * D);
   const bf16_t* W2 = a.w2_k + (int64_t)h * DP * HID;
 

@@ -39,6 +39,13 @@ WORKLOADS = {
     "wan480p_cfg_c3": Workload("wan480p_cfg_c3", B=2, H=12, d=128, T=21, HW=30 * 52, chunk=3),
     "wan480p_long": Workload("wan480p_long", B=1, H=12, d=128, T=41, HW=30 * 52, chunk=1),
     "wan720p": Workload("wan720p", B=1, H=12, d=128, T=21, HW=45 * 80, chunk=1, rms_norm=False),
+    # 320x480 generation (20 x 30 latent tokens per frame), the shape of the paper's
+    # on-device tables (section 4.2): 21 to 41 latent frames, T_c = 3, and the larger
+    # chunk sizes of the T_c ablation
+    "p320_t21_c3": Workload("p320_t21_c3", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=3),
+    "p320_t41_c3": Workload("p320_t41_c3", B=1, H=12, d=128, T=41, HW=20 * 30, chunk=3),
+    "p320_t21_c5": Workload("p320_t21_c5", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=5),
+    "p320_t21_c7": Workload("p320_t21_c7", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=7),
 }
 
 

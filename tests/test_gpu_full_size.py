@@ -73,6 +73,14 @@ def test_wan480p_overlap_one_frame():
     check_workload("wan480p_cfg_c3", heads=[2], batches=(1,), overlap=1)
 
 
+@pytest.mark.parametrize("name,overlap", [("p320_t21_c3", 0), ("p320_t21_c3", 1), ("p320_t41_c3", 1),
+                                          ("p320_t21_c5", 0), ("p320_t21_c7", 2)])
+def test_320x480_shapes(name, overlap):
+    """20 x 30 latent tokens per frame, 21 and 41 frames, T_c in {3, 5, 7} (the
+    last chunk of T_c = 5 is a single frame), with and without overlap."""
+    check_workload(name, heads=[4, 9], overlap=overlap, debug=(overlap == 1))
+
+
 def test_long_video_flat_workspace():
     """Doubling the latent frames leaves the workspace untouched (section 3.3,
     point 3): the same caller-owned buffer serves T=21 and T=41, the library

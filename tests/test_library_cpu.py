@@ -108,6 +108,17 @@ def test_forward_argument_validation_without_gpu():
     assert st(None, 1, P(ok), 1, 1, 1, 2, 4, 8, 64, 2, None) == binding.E_NULL
     assert st(1, 1, P(ok), 1, 1, 1, 2, 4, 8, 64, 5, None) == binding.E_SHAPE
     assert st(1, 1, P(ok), 1, 1, 1, 2, 4, 8, 64, -1, None) == binding.E_SHAPE
+    # rehyat_step(q_t, k_win, v_win, phi, S, z, out_t, B, H, d, n_q, n_win, n_absorb, stab, stream)
+    sp = lambda *a: lib.rehyat_step(*a)
+    assert sp(1, 1, 1, P(ok), 1, None, 1, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
+    assert sp(1, None, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
+    assert sp(1, 1, 1, None, 1, 1, 1, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
+    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, 17, 0, None) == binding.E_SHAPE   # absorbs more than the window
+    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, -1, 0, None) == binding.E_SHAPE
+    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 0, 16, 8, 0, None) == binding.E_SHAPE
+    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 0, 0, 0, None) == binding.E_SHAPE
+    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, 8, 3, None) == binding.E_SHAPE    # unknown stabiliser
+    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 96, 8, 16, 8, 0, None) == binding.E_UNSUPPORTED
 
 
 def test_set_workspace_rejects_misaligned_pointer():
