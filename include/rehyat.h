@@ -128,8 +128,11 @@ int rehyat_forward(const void *q, const void *k, const void *v,
  * Same operator with the remaining knobs of the paper:
  *   overlap   : T_o latent frames by which the softmax window reaches back
  *               (Eq. 12); the state then lags by the same amount (Eq. 13)
- *   causal    : 1 = Eq. 13 (built).  0 = the bidirectional sets of Eq. 11-12:
- *               REHYAT_E_UNSUPPORTED in this build
+ *   causal    : 1 = Eq. 13.  0 = the bidirectional sets of Eq. 11-12: the
+ *               linear part of chunk t covers every token outside its softmax
+ *               window, before and after (the whole K, V are read before the
+ *               first output; REHYAT_E_UNSUPPORTED if min(chunk + overlap, T)
+ *               exceeds 64 frames)
  *   stab_mode : REHYAT_STAB_ROWMAX or REHYAT_STAB_NONE
  *   debug     : NULL, or HOST pointer to the component outputs
  */

@@ -199,6 +199,126 @@ int launch_prefix_window(char* ws, const WsLayout& L, int B, int H, int d, int d
   return REHYAT_OK;
 }
 
+int launch_attn_window(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                       void* out, const rehyat_debug_out* debug, char* ws, const WsLayout& L, int B,
+                       int H, int T, int HW, int d, int chunk, int overlap, int c0, int n_chunks,
+                       int qtiles, int stab_mode, bool bidir, hipStream_t st) {
+  AttnArgs a;
+  a.q = (const bf16_t*)q;
+  a.k = (const bf16_t*)k;
+  a.v = (const bf16_t*)v;
+  a.out = (bf16_t*)out;
+  a.w1_q = (const bf16_t*)phi->w1_q;
+  a.b1_q = (const float*)phi->b1_q;
+  a.w2_q = (const bf16_t*)phi->w2_q;
+  a.b2_q = (const float*)phi->b2_q;
+  a.state_s = (const bf16_t*)(ws + L.state_s);
+  a.state_z = (const float*)(ws + L.state_z);
+  a.dbg_m = debug ? debug->m : nullptr;
+  a.dbg_nS = debug ? debug->nS : nullptr;
+  a.dbg_aS = debug ? debug->aS : nullptr;
+  a.dbg_nL = debug ? debug->nL : nullptr;
+  a.dbg_aL = debug ? debug->aL : nullptr;
+  a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)d));
+  a.H = H;
+  a.T = T;
+  a.HW = HW;
+  a.chunk = chunk;
+  a.overlap = overlap;
+  a.chunk0 = c0;
+  a.n_win_chunks = n_chunks;
+  a.qtiles = qtiles;
+  a.state_slots = kStateSlots;
+  a.stab_mode = stab_mode;
+  a.n_items = B * H * n_chunks * qtiles;
+  a.items_per_xcd = (a.n_items + 7) / 8;
+  a.q_bh_stride = a.kv_bh_stride = (int64_t)T * HW * d;
+  a.step_nq = a.step_nwin = 0;
+  a.all_linear = bidir ? 1 : 0;
+  hipError_t e;
+  {
+    ProfScope prof(2, st);
+    e = launch_attn(a, d, a.items_per_xcd * 8, st);
+  }
+  if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
+  return REHYAT_OK;
+}
+
+// Bidirectional sets (Eq. 11-12): the linear part of chunk t covers every token outside
+// its softmax window.  Per-frame sums F(f) of phi_k(k) v^T come from the chunk-state kernel
+// run with one-frame segments; state(t) = sum_f F(f) - sum_{f in window t} F(f).
+int forward_bidirectional(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                          void* out, const rehyat_debug_out* debug, char* ws, const WsLayout& L,
+                          int B, int H, int T, int HW, int d, int dp, int chunk, int overlap,
+                          int stab_mode, hipStream_t st) {
+  const int nc = num_chunks(T, chunk);
+  const int chunk_frames = chunk < T ? chunk : T;
+  const int qtile = attn_query_tile(d);
+  const int qtiles = (int)(((int64_t)chunk_frames * HW + qtile - 1) / qtile);
+  if (nc == 1)  // the window is the whole sequence: plain softmax attention
+    return launch_attn_window(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, chunk, overlap, 0, 1,
+                              qtiles, stab_mode, false, st);
+  int win_frames = chunk + overlap;  // frames one window can span
+  if (win_frames > T) win_frames = T;
+  if (win_frames > kPartialSlots) return REHYAT_E_UNSUPPORTED;
+  int nsplit = choose_nsplit(B * H, T);
+  while (nsplit > 1 && kPartialSlots / nsplit < win_frames) --nsplit;
+  const int fwin = kPartialSlots / nsplit;  // frames whose sums fit the partial slots
+
+  // pass 1: total over all frames, left in the carry
+  for (int f0 = 0; f0 < T; f0 += fwin) {
+    const int n = (T - f0 < fwin) ? T - f0 : fwin;
+    int rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, 1, 0, f0, n, nsplit, st);
+    if (rc != REHYAT_OK) return rc;
+    rc = launch_prefix_window(ws, L, B, H, d, dp, /*n_chunks=*/0, /*n_seg=*/n, nsplit, f0 == 0, st);
+    if (rc != REHYAT_OK) return rc;
+  }
+  const bool resident = T <= fwin;  // every F(f) is still in the partial slots
+
+  // pass 2: windows of chunks whose frames fit the partial slots together
+  int cw = (fwin - overlap) / chunk;
+  if (cw < 1) cw = 1;
+  if (cw > kStateSlots) cw = kStateSlots;
+  for (int c0 = 0; c0 < nc; c0 += cw) {
+    const int c1 = (c0 + cw < nc) ? c0 + cw : nc;
+    int F0 = c0 * chunk - overlap;
+    if (F0 < 0) F0 = 0;
+    int F1 = c1 * chunk;
+    if (F1 > T) F1 = T;
+    if (!resident) {
+      int rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, 1, 0, F0, F1 - F0, nsplit, st);
+      if (rc != REHYAT_OK) return rc;
+    }
+    BidirArgs b;
+    b.partial = (const float*)(ws + L.partial);
+    b.total = (const float*)(ws + L.carry);
+    b.state_s = (bf16_t*)(ws + L.state_s);
+    b.state_z = (float*)(ws + L.state_z);
+    b.BH = B * H;
+    b.T = T;
+    b.chunk = chunk;
+    b.overlap = overlap;
+    b.chunk0 = c0;
+    b.n_chunks = c1 - c0;
+    b.frame0 = resident ? 0 : F0;
+    b.nsplit = nsplit;
+    b.partial_slots = kPartialSlots;
+    b.state_slots = kStateSlots;
+    b.elems = d * dp + dp;
+    b.s_elems = d * dp;
+    hipError_t e;
+    {
+      ProfScope prof(1, st);
+      e = launch_bidir_state(b, st);
+    }
+    if (e != hipSuccess) return hip_fail(e, "bidirectional state kernel launch");
+    int rc = launch_attn_window(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, chunk, overlap, c0,
+                                c1 - c0, qtiles, stab_mode, true, st);
+    if (rc != REHYAT_OK) return rc;
+  }
+  return REHYAT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -284,7 +404,6 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
   if (rc != REHYAT_OK) return rc;
   if (stab_mode != REHYAT_STAB_ROWMAX && stab_mode != REHYAT_STAB_NONE) return REHYAT_E_SHAPE;
   if (causal != 0 && causal != 1) return REHYAT_E_SHAPE;
-  if (causal == 0) return REHYAT_E_UNSUPPORTED;
   const int dp = phi->dprime;
   hipStream_t st = (hipStream_t)stream;
 
@@ -293,6 +412,9 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
   char* ws = nullptr;
   rc = ensure_workspace(L.total, &ws);
   if (rc != REHYAT_OK) return rc;
+  if (causal == 0)
+    return forward_bidirectional(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, dp, chunk, overlap,
+                                 stab_mode, st);
 
   const int nc = num_chunks(T, chunk);
   const int nsplit = choose_nsplit(B * H, nc - 1);
@@ -314,43 +436,9 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
       rc = launch_prefix_window(ws, L, B, H, d, dp, n_chunks, n_seg, nsplit, c0 == 0, st);
       if (rc != REHYAT_OK) return rc;
     }
-    AttnArgs a;
-    a.q = (const bf16_t*)q;
-    a.k = (const bf16_t*)k;
-    a.v = (const bf16_t*)v;
-    a.out = (bf16_t*)out;
-    a.w1_q = (const bf16_t*)phi->w1_q;
-    a.b1_q = (const float*)phi->b1_q;
-    a.w2_q = (const bf16_t*)phi->w2_q;
-    a.b2_q = (const float*)phi->b2_q;
-    a.state_s = (const bf16_t*)(ws + L.state_s);
-    a.state_z = (const float*)(ws + L.state_z);
-    a.dbg_m = debug ? debug->m : nullptr;
-    a.dbg_nS = debug ? debug->nS : nullptr;
-    a.dbg_aS = debug ? debug->aS : nullptr;
-    a.dbg_nL = debug ? debug->nL : nullptr;
-    a.dbg_aL = debug ? debug->aL : nullptr;
-    a.scale_log2e = (float)(1.4426950408889634 / std::sqrt((double)d));
-    a.H = H;
-    a.T = T;
-    a.HW = HW;
-    a.chunk = chunk;
-    a.overlap = overlap;
-    a.chunk0 = c0;
-    a.n_win_chunks = n_chunks;
-    a.qtiles = qtiles;
-    a.state_slots = kStateSlots;
-    a.stab_mode = stab_mode;
-    a.n_items = B * H * n_chunks * qtiles;
-    a.items_per_xcd = (a.n_items + 7) / 8;
-    a.q_bh_stride = a.kv_bh_stride = (int64_t)T * HW * d;
-    a.step_nq = a.step_nwin = 0;
-    hipError_t e;
-    {
-      ProfScope prof(2, st);
-      e = launch_attn(a, d, a.items_per_xcd * 8, st);
-    }
-    if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
+    rc = launch_attn_window(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, chunk, overlap, c0,
+                            n_chunks, qtiles, stab_mode, /*bidir=*/false, st);
+    if (rc != REHYAT_OK) return rc;
   }
   return REHYAT_OK;
 }
@@ -485,6 +573,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   a.kv_bh_stride = (int64_t)n_win * d;
   a.step_nq = n_q;
   a.step_nwin = n_win;
+  a.all_linear = 0;
   {
     ProfScope prof(2, st);
     e = launch_attn(a, d, a.items_per_xcd * 8, st);

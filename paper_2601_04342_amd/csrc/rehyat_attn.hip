@@ -297,6 +297,7 @@ attn_kernel(AttnArgs a) {
     cr.l_hi = 1;
   } else {
     cr = chunk_range(a.T, a.HW, a.chunk, a.overlap, t);
+    if (a.all_linear) cr.l_hi = 1;
   }
   const int64_t q0 = cr.q_lo + (int64_t)qt * C::QT;
   if (q0 >= cr.q_hi) return;  // short last chunk: fewer query tiles

@@ -71,6 +71,7 @@ struct AttnArgs {
   int step_nq, step_nwin;  // step_nq > 0 (streaming step): queries are rows [0, step_nq) of q,
                            // the softmax window is rows [0, step_nwin) of k / v, the linear
                            // state is slot 0; the frame geometry above is then unused
+  int all_linear;          // 1: every chunk reads a state (bidirectional sets of Eq. 11-12)
 };
 
 // ---- transposes the carry into the [dprime][d] layout of the public state hook ----
@@ -79,6 +80,22 @@ struct StateOutArgs {
   float* S_out;        // [BH, dprime, d]
   float* z_out;        // [BH, dprime]
   int BH, d, dprime;
+};
+
+// ---- bidirectional states: everything outside each chunk's softmax window -----------
+// state(c) = total - sum of the per-frame sums of the frames inside window c (Eq. 11-12);
+// the per-frame sums of frames [frame0, frame0 + n_frames) are in `partial`
+// (frame-major, nsplit pieces each), the total over all frames is in `total`.
+struct BidirArgs {
+  const float* partial;
+  const float* total;    // [BH, d*dprime + dprime]
+  bf16_t* state_s;       // [BH, state_slots, d, dprime]
+  float* state_z;        // [BH, state_slots, dprime]
+  int BH, T, chunk, overlap;
+  int chunk0, n_chunks;  // chunks of this window -> state slots 0 .. n_chunks-1
+  int frame0;            // first frame held in `partial`
+  int nsplit, partial_slots, state_slots;
+  int elems, s_elems;
 };
 
 // ---- caller's state [dprime][d] + z into the carry layout (inverse of StateOutArgs) ----
@@ -95,5 +112,6 @@ hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream);
 int attn_query_tile(int d);  // query tokens per workgroup of the attention kernel
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream);
 hipError_t launch_state_in(const StateInArgs& a, hipStream_t stream);
+hipError_t launch_bidir_state(const BidirArgs& a, hipStream_t stream);
 
 }  // namespace rehyat

@@ -21,15 +21,18 @@ prefix_kernel(PrefixArgs a) {
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
   if (!a.first_window) acc = *reinterpret_cast<const f32x4*>(carry);
   const bool is_s = idx < a.s_elems;
-  for (int c = 0; c < a.n_chunks; ++c) {
-    if (is_s) {
-      u32x2 pk;
-      pk[0] = pack_bf16(acc[0], acc[1]);
-      pk[1] = pack_bf16(acc[2], acc[3]);
-      *reinterpret_cast<u32x2*>(a.state_s + ((int64_t)bh * a.state_slots + c) * a.s_elems + idx) = pk;
-    } else {
-      *reinterpret_cast<f32x4*>(a.state_z + ((int64_t)bh * a.state_slots + c) * (a.elems - a.s_elems) +
-                                (idx - a.s_elems)) = acc;
+  const int n_steps = a.n_chunks > a.n_seg ? a.n_chunks : a.n_seg;
+  for (int c = 0; c < n_steps; ++c) {
+    if (c < a.n_chunks) {
+      if (is_s) {
+        u32x2 pk;
+        pk[0] = pack_bf16(acc[0], acc[1]);
+        pk[1] = pack_bf16(acc[2], acc[3]);
+        *reinterpret_cast<u32x2*>(a.state_s + ((int64_t)bh * a.state_slots + c) * a.s_elems + idx) = pk;
+      } else {
+        *reinterpret_cast<f32x4*>(a.state_z + ((int64_t)bh * a.state_slots + c) * (a.elems - a.s_elems) +
+                                  (idx - a.s_elems)) = acc;
+      }
     }
     if (c < a.n_seg) {
       for (int sp = 0; sp < a.nsplit; ++sp) {
@@ -39,6 +42,38 @@ prefix_kernel(PrefixArgs a) {
     }
   }
   *reinterpret_cast<f32x4*>(carry) = acc;
+}
+
+__global__ void __launch_bounds__(256)
+bidir_state_kernel(BidirArgs a) {
+  const int bh = blockIdx.y;
+  const int idx = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= a.elems) return;
+  const float* part = a.partial + (int64_t)bh * a.partial_slots * a.elems + idx;
+  const f32x4 total = *reinterpret_cast<const f32x4*>(a.total + (int64_t)bh * a.elems + idx);
+  const bool is_s = idx < a.s_elems;
+  for (int c = 0; c < a.n_chunks; ++c) {
+    const int t = a.chunk0 + c;
+    // frames of the softmax window of chunk t (Eq. 12)
+    int f_lo = t * a.chunk - a.overlap;
+    if (f_lo < 0) f_lo = 0;
+    int f_hi = (t + 1) * a.chunk;
+    if (f_hi > a.T) f_hi = a.T;
+    f32x4 w = {0.f, 0.f, 0.f, 0.f};
+    for (int f = f_lo; f < f_hi; ++f)
+      for (int sp = 0; sp < a.nsplit; ++sp)
+        w += *reinterpret_cast<const f32x4*>(part + (int64_t)((f - a.frame0) * a.nsplit + sp) * a.elems);
+    const f32x4 acc = total - w;
+    if (is_s) {
+      u32x2 pk;
+      pk[0] = pack_bf16(acc[0], acc[1]);
+      pk[1] = pack_bf16(acc[2], acc[3]);
+      *reinterpret_cast<u32x2*>(a.state_s + ((int64_t)bh * a.state_slots + c) * a.s_elems + idx) = pk;
+    } else {
+      *reinterpret_cast<f32x4*>(a.state_z + ((int64_t)bh * a.state_slots + c) * (a.elems - a.s_elems) +
+                                (idx - a.s_elems)) = acc;
+    }
+  }
 }
 
 __global__ void __launch_bounds__(256)
@@ -76,6 +111,12 @@ hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream) {
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream) {
   dim3 grid((a.d * a.dprime + 255) / 256, a.BH);
   hipLaunchKernelGGL(state_out_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_bidir_state(const BidirArgs& a, hipStream_t stream) {
+  dim3 grid((a.elems / 4 + 255) / 256, a.BH);
+  hipLaunchKernelGGL(bidir_state_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 

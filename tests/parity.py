@@ -76,16 +76,17 @@ def linear_share(ref, stab=0):
 
 
 def run_case(B, H, T, HW, d, chunk, overlap=0, stab=0, gain=1.0, rms=True, seed=0,
-             debug=True, phi=None):
+             debug=True, phi=None, causal=True):
     N = T * HW
     q, k, v = synth.make_qkv(B, H, N, d, seed=seed, rms_norm=rms)
     if phi is None:
         phi = synth.make_phi(H, d, seed=seed + 1, gain=gain)
     dq, dk, dv, dphi = to_device(q, k, v, phi)
     res = binding.forward(dq, dk, dv, dphi, T, HW, chunk, overlap=overlap, stab_mode=stab,
-                          debug=debug)
+                          debug=debug, causal=causal)
     torch.cuda.synchronize()
     out, comps = res if debug else (res, None)
-    ref = cref.forward(*oracle_inputs(q, k, v, phi), T, HW, chunk, overlap=overlap, stab=stab)
-    label = f"B{B} H{H} T{T} HW{HW} d{d} chunk{chunk} ov{overlap} stab{stab} gain{gain}"
+    ref = cref.forward(*oracle_inputs(q, k, v, phi), T, HW, chunk, overlap=overlap, stab=stab,
+                       causal=causal)
+    label = f"B{B} H{H} T{T} HW{HW} d{d} chunk{chunk} ov{overlap} stab{stab} gain{gain} causal{causal}"
     return compare(out, comps, ref, stab=stab, label=label), ref

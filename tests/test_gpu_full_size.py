@@ -24,15 +24,16 @@ def sample_rows(w, overlap=0, n_random=24, seed=0):
     return np.array(sorted(r for r in rows if 0 <= r < w.N), dtype=np.int64)
 
 
-def check_workload(name, heads, batches=(0,), overlap=0, debug=False, gain=1.0):
+def check_workload(name, heads, batches=(0,), overlap=0, debug=False, gain=1.0, causal=True):
     w = synth.WORKLOADS[name]
     print(f"[gpu-test] full size {name} heads {heads} batches {batches} gain {gain}", flush=True)
     q, k, v, phi = synth.make_workload(w, gain=gain)
     dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
-    if overlap == 0 and not debug:
+    if overlap == 0 and not debug and causal:
         out, comps = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, plain=True), None
     else:
-        res = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, overlap=overlap, debug=debug)
+        res = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, overlap=overlap, debug=debug,
+                              causal=causal)
         out, comps = res if debug else (res, None)
     torch.cuda.synchronize()
     assert torch.isfinite(out.float()).all()
@@ -41,7 +42,7 @@ def check_workload(name, heads, batches=(0,), overlap=0, debug=False, gain=1.0):
     for b in batches:
         for h in heads:
             ref = cref.forward(*parity.oracle_inputs(q, k, v, phi, heads=[h], batch=b),
-                               w.T, w.HW, w.chunk, overlap=overlap, rows=rows)
+                               w.T, w.HW, w.chunk, overlap=overlap, rows=rows, causal=causal)
             c = None if comps is None else {n: t[b:b + 1, h:h + 1] for n, t in comps.items()}
             e = parity.compare(out[b:b + 1, h:h + 1], c, ref, rows=rows, label=f"{name} b{b} h{h}")
             worst = (max(worst[0], e[0]), max(worst[1], e[1]))
@@ -79,6 +80,12 @@ def test_320x480_shapes(name, overlap):
     """20 x 30 latent tokens per frame, 21 and 41 frames, T_c in {3, 5, 7} (the
     last chunk of T_c = 5 is a single frame), with and without overlap."""
     check_workload(name, heads=[4, 9], overlap=overlap, debug=(overlap == 1))
+
+
+@pytest.mark.parametrize("name,overlap", [("wan480p", 0), ("wan480p_long", 1), ("p320_t21_c3", 1)])
+def test_bidirectional_full_size(name, overlap):
+    """Eq. 11-12 at the bench shapes (the paper's causality ablation, Table 6)."""
+    check_workload(name, heads=[6], overlap=overlap, debug=True, gain=0.35, causal=False)
 
 
 def test_long_video_flat_workspace():

@@ -60,6 +60,33 @@ def test_small_shapes_match_oracle(case):
           f"{parity.linear_share(ref, stab):.2f}", flush=True)
 
 
+BIDIR_CASES = [
+    # B, H, T, HW, d, chunk, overlap, stab, gain
+    (1, 2, 4, 64, 64, 1, 0, 0, 8.0),
+    (2, 3, 5, 77, 128, 2, 0, 0, 4.0),      # short last chunk
+    (1, 2, 5, 77, 128, 2, 1, 0, 4.0),      # overlapping windows
+    (1, 2, 7, 50, 64, 3, 2, 0, 6.0),
+    (1, 2, 4, 30, 64, 1, 3, 0, 6.0),       # the last window is the whole sequence: empty linear set
+    (1, 2, 5, 77, 64, 1, 0, 1, 4.0),       # stabiliser off
+    (1, 1, 3, 100, 128, 3, 0, 0, 1.0),     # one chunk: plain softmax attention
+    (1, 1, 4, 2000, 128, 1, 0, 0, 2.0),    # frames are split into pieces
+    (1, 2, 70, 20, 64, 1, 0, 0, 3.0),      # more frames than partial slots: two passes
+    (1, 1, 75, 12, 128, 2, 1, 0, 3.0),     # two passes + overlap + short last chunk
+    (1, 1, 2, 40, 128, 1, 0, 0, 5.0),      # two chunks: each one's linear set is the other
+]
+
+
+@pytest.mark.parametrize("case", BIDIR_CASES)
+def test_bidirectional_small_shapes_match_oracle(case):
+    """Non-causal sets of Eq. 11-12: the linear part covers the tokens on both
+    sides of the softmax window."""
+    B, H, T, HW, d, chunk, overlap, stab, gain = case
+    (emax, emean), ref = parity.run_case(B, H, T, HW, d, chunk, overlap, stab, gain,
+                                         seed=sum(case[:6]) + 1, causal=False)
+    print(f"   max-abs {emax:.2e} mean-abs {emean:.2e} linear share "
+          f"{parity.linear_share(ref, stab):.2f}", flush=True)
+
+
 def test_zero_phi_is_block_diagonal_softmax():
     """phi = 0 isolates the softmax kernel: chunk-local softmax attention."""
     B, H, T, HW, d = 1, 2, 3, 200, 128

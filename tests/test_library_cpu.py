@@ -101,7 +101,6 @@ def test_forward_argument_validation_without_gpu():
     ex = lambda *a: lib.rehyat_forward_ex(*a)
     base = (1, 1, 1, P(ok), 1, 1, 2, 4, 8, 64, 1)
     assert ex(*base, -1, 1, 0, None, None) == binding.E_SHAPE       # negative overlap
-    assert ex(*base, 0, 0, 0, None, None) == binding.E_UNSUPPORTED  # bidirectional form
     assert ex(*base, 0, 2, 0, None, None) == binding.E_SHAPE
     assert ex(*base, 0, 1, 7, None, None) == binding.E_SHAPE        # unknown stabiliser
     st = lambda *a: lib.rehyat_state(*a)
