@@ -24,16 +24,20 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 ATTN_TRAFFIC_BYTES = {"wan480p": 454863744}
 
 
-def algorithmic_flops(w, overlap=0):
+def algorithmic_flops(w, overlap=0, causal=True):
     """Work the method itself requires (no padding, no unused last-chunk state,
-    no phi_q / read-out for chunk 0 whose linear set is empty)."""
+    no phi_q / read-out for chunks whose linear set is empty)."""
     from paper_2601_04342_amd import binding
     plan = binding.chunk_plan(w.T, w.HW, w.chunk, overlap).tolist()
     BH, d, h, Dp = w.B * w.H, w.d, 2 * w.d, 2 * w.d
     softmax = 4 * d * BH * sum((r[1] - r[0]) * (r[3] - r[2]) for r in plan)
     phi_tok = 2 * (d * h + h * Dp)                      # one map, one token
-    n_lin_q = sum(r[1] - r[0] for r in plan if r[4] > 0)  # queries with a linear set
-    n_state = plan[-1][4]                               # tokens ever absorbed
+    if causal:
+        n_lin_q = sum(r[1] - r[0] for r in plan if r[4] > 0)  # queries with a linear set
+        n_state = plan[-1][4]                               # tokens ever absorbed
+    else:   # every token outside the window: empty only when the window is everything
+        n_lin_q = sum(r[1] - r[0] for r in plan if r[3] - r[2] < w.N)
+        n_state = w.N if n_lin_q else 0
     phi_q = BH * n_lin_q * phi_tok
     phi_k = BH * n_state * phi_tok
     state = 2 * BH * n_state * Dp * (d + 1)
@@ -66,6 +70,11 @@ def main():
     ap.add_argument("--workload", default="wan480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=12)
+    ap.add_argument("--mode", choices=("forward", "bidirectional", "stream"), default="forward",
+                    help="forward: rehyat_forward (the headline path); bidirectional: "
+                         "rehyat_forward_ex(causal=0); stream: one rehyat_step per chunk with "
+                         "caller-owned state and window")
+    ap.add_argument("--overlap", type=int, default=0, help="T_o (bidirectional and stream modes)")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="after the timed steps also run one plain device-to-device copy of this "
                          "many MiB (a kernel of known HBM traffic that calibrates the FETCH_SIZE / "
@@ -87,7 +96,31 @@ def main():
     dq, dk, dv = (x.to("cuda", torch.bfloat16).contiguous() for x in (q, k, v))
     dphi = binding.phi_to_device(phi)
     out = torch.empty_like(dq)
-    step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, out=out, plain=True)
+    causal = args.mode != "bidirectional"
+    overlap = args.overlap if args.mode != "forward" else 0
+    if args.mode == "forward":
+        step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, out=out, plain=True)
+    elif args.mode == "bidirectional":
+        step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, out=out,
+                                       overlap=overlap, causal=False)
+    else:
+        # the caller's side of chunk-by-chunk generation: per chunk its queries, its K/V
+        # window and the number of tokens that leave the window, prepared outside the timing
+        plan = binding.chunk_plan(w.T, w.HW, w.chunk, overlap).tolist()
+        pieces = []
+        for t, (q_lo, q_hi, s_lo, s_hi, _) in enumerate(plan):
+            n_absorb = plan[t + 1][2] - s_lo if t + 1 < len(plan) else 0
+            pieces.append((dq[:, :, q_lo:q_hi].contiguous(), dk[:, :, s_lo:s_hi].contiguous(),
+                           dv[:, :, s_lo:s_hi].contiguous(), torch.empty_like(dq[:, :, q_lo:q_hi]),
+                           n_absorb))
+        S = torch.zeros(w.B, w.H, 2 * w.d, w.d, device="cuda")
+        z = torch.zeros(w.B, w.H, 2 * w.d, device="cuda")
+
+        def step():
+            S.zero_()
+            z.zero_()
+            for q_t, k_w, v_w, o_t, n_absorb in pieces:
+                binding.step(q_t, k_w, v_w, dphi, S, z, n_absorb, out=o_t)
 
     for _ in range(args.warmup):
         step()
@@ -101,6 +134,8 @@ def main():
     dt = time.perf_counter() - t0
     prof = binding.profile_read()
     binding.profile_enable(False)
+    if args.mode == "stream":
+        out = torch.cat([p[3] for p in pieces], dim=2)
     assert torch.isfinite(out.float()).all()
     if args.pmc_copy_mib > 0:
         src = torch.full((args.pmc_copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
@@ -111,9 +146,10 @@ def main():
         del src, dst
 
     ms = dt * 1e3 / args.steps
-    fl = algorithmic_flops(w)
+    fl = algorithmic_flops(w, overlap, causal)
     kern_ms = {kk: (tot / n if n else None) for kk, (tot, n) in prof.items()}
-    attn_ms = kern_ms["attn"]
+    # all launches of the attention kernel in one step share the step's algorithmic work
+    attn_ms = prof["attn"][0] / args.steps
     achieved = fl["attn_kernel"] / (attn_ms * 1e-3) / 1e12
     res = {
         "metric": "hybrid-attn tokens/s per layer @Wan2.1-480p shape; TFLOP/s and % MFMA peak",
@@ -122,7 +158,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} T={w.T} HW={w.HW} "
-                               f"N={w.N} chunk={w.chunk} overlap=0 causal row-max",
+                               f"N={w.N} chunk={w.chunk} overlap={overlap} "
+                               f"{'causal' if causal else 'bidirectional'} row-max"
+                               + (", one rehyat_step per chunk" if args.mode == "stream" else ""),
                    "phi": "hidden=D'=2d, degree 2, ReLU, N(0,0.02) seed 1",
                    "qkv": "N(0,1) seed 0, q,k RMS-normalised, bf16"},
         "tflops": fl["total"] / (ms * 1e-3) / 1e12,
@@ -134,9 +172,9 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "attn_kernel<128, 1>", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES.get(w.name)},
-        "state_kernel_tflops": (fl["state_kernel"] / (kern_ms["state"] * 1e-3) / 1e12
-                                if kern_ms["state"] else None),
+                     "traffic": ATTN_TRAFFIC_BYTES.get(w.name) if args.mode == "forward" else None},
+        "state_kernel_tflops": (fl["state_kernel"] / (prof["state"][0] / args.steps * 1e-3) / 1e12
+                                if prof["state"][1] else None),
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, q, k, v, phi, args.cpu_heads)
