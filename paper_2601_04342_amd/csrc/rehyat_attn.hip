@@ -274,7 +274,7 @@ attn_kernel(AttnArgs a) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform for the compiler too
   const int g = lane >> 5;
   const int r = lane & 31;
 
@@ -310,6 +310,9 @@ attn_kernel(AttnArgs a) {
 
   // ---- queries of this wave, held as B operands ---------------------------
   const int64_t qw0 = q0 + wave * C::QW;
+  // a wave whose 32 queries all lie beyond the chunk (last query tile) still moves its
+  // share of every tile and meets every barrier, but computes nothing
+  const bool wave_live = qw0 < cr.q_hi;
   bf16x8 Qr[QB][KS];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
@@ -348,10 +351,10 @@ attn_kernel(AttnArgs a) {
     const char* const Vb = reinterpret_cast<const char*>(Vg + s_lo * D);
     auto contiguous = [](int R) { return R * (2 * D); };
     // K and V of tile `it` into the given buffers
+    const __amdgpu_buffer_rsrc_t Kr = make_rsrc(Kb), Vr = make_rsrc(Vb);
     auto issue_kv = [&](int it, char* kd, char* vd) {
-      const int64_t goff = (int64_t)it * TB;
-      tile_load_direct<2 * D, TB, 4>(Kb + goff, kd, wave, lane, contiguous);
-      tile_load_direct<2 * D, TB, 4>(Vb + goff, vd, wave, lane, contiguous);
+      tile_load_buffer<2 * D, TB, 4>(Kr, it * TB, kd, wave, lane, contiguous);
+      tile_load_buffer<2 * D, TB, 4>(Vr, it * TB, vd, wave, lane, contiguous);
     };
     if (n_full > 0) issue_kv(0, A0, A2);
       // per-head vectors of phase L (their loads complete long before phase L, whose
@@ -371,11 +374,11 @@ attn_kernel(AttnArgs a) {
     // for every wave, by the barrier that ends tile it.
     for (int it = 0; it < n_full; it += 2) {
       if (it + 1 < n_full) issue_kv(it + 1, A1, A3);
-      softmax_tile<D, QB, false>(A0, A2, fo, Qr, O, mrun, lrun, sc, 64, lane);
+      if (wave_live) softmax_tile<D, QB, false>(A0, A2, fo, Qr, O, mrun, lrun, sc, 64, lane);
       wait_loads_and_barrier<0>();
       if (it + 1 < n_full) {
         if (it + 2 < n_full) issue_kv(it + 2, A0, A2);
-        softmax_tile<D, QB, false>(A1, A3, fo, Qr, O, mrun, lrun, sc, 64, lane);
+        if (wave_live) softmax_tile<D, QB, false>(A1, A3, fo, Qr, O, mrun, lrun, sc, 64, lane);
         wait_loads_and_barrier<0>();
       }
     }
@@ -388,7 +391,7 @@ attn_kernel(AttnArgs a) {
       tile_load_direct<2 * D, TB, 4>(Kb + goff, A0, wave, lane, clamped);
       tile_load_direct<2 * D, TB, 4>(Vb + goff, A2, wave, lane, clamped);
       wait_loads_and_barrier<0>();
-      softmax_tile<D, QB, true>(A0, A2, fo, Qr, O, mrun, lrun, sc, rem, lane);
+      if (wave_live) softmax_tile<D, QB, true>(A0, A2, fo, Qr, O, mrun, lrun, sc, rem, lane);
       wait_loads_and_barrier<0>();
     }
   }
@@ -442,15 +445,16 @@ attn_kernel(AttnArgs a) {
     const char* W2 = reinterpret_cast<const char*>(a.w2_q + (int64_t)h * DP * HID);
     const char* St = reinterpret_cast<const char*>(a.state_s + ((int64_t)bh * a.state_slots + tc) * (int64_t)D * DP);
 
+    const __amdgpu_buffer_rsrc_t W1r = make_rsrc(W1), W2r = make_rsrc(W2), Str = make_rsrc(St);
     auto issue_tile = [&](auto KIND, int idx, char* dst) {
       constexpr int kind = decltype(KIND)::value;
       if constexpr (kind == kW1) {
-        tile_load_direct<2 * D, TB, 4>(W1 + idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
+        tile_load_buffer<2 * D, TB, 4>(W1r, idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
       } else if constexpr (kind == kW2) {
-        tile_load_direct<2 * D, TB, 4>(W2 + idx * 32 * (4 * D), dst, wave, lane,
-                                    [](int R) { return (R & 31) * (4 * D) + (R >> 5) * (2 * D); });
+        tile_load_buffer<2 * D, TB, 4>(W2r, idx * 32 * (4 * D), dst, wave, lane,
+                                       [](int R) { return (R & 31) * (4 * D) + (R >> 5) * (2 * D); });
       } else {
-        tile_load_direct<128, TB, 4>(St + idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
+        tile_load_buffer<128, TB, 4>(Str, idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
       }
     };
     auto buf = [&](auto I) -> char* {
@@ -493,6 +497,7 @@ attn_kernel(AttnArgs a) {
       constexpr LinStep sd = LinStepC<D, st>::value;
       wait_loads_and_barrier<sd.younger * LPT>();
       issue_all(LinStepC<D, st>{});
+      if (!wave_live) return;  // this step of this wave only (the lambda is one step)
       if constexpr (st < NW1) {
         // ---- two 32-row blocks of hidden units ------------------------------------
         const char* Ws = buf(std::integral_constant<int, sd.buf_w>{});

@@ -220,6 +220,38 @@ __device__ __forceinline__ void tile_load_direct(const char* gbase, char* lds_ti
   }
 }
 
+// Raw buffer descriptor for direct loads.  The hardware's range check covers only
+// the per-lane offset (never the scalar offset), so the descriptor is left open
+// ended and callers keep every access inside their tensors themselves.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0x7fffffff, 0x00020000);
+}
+
+// Same tile fill as tile_load_direct for row maps that split into a block part and a
+// row-in-block part, rowaddr(blk * RPB + j) == rowaddr(blk * RPB) + rowaddr(j) for j < RPB
+// (RPB = rows per 1 KB block): the per-lane offset is then the same for every block a
+// wave moves, and the block part, the tile offset `soff` (bytes from the descriptor's
+// base) and the LDS address are all wave-uniform, so a load costs no vector ALU work.
+// `wave` must be wave-uniform in the compiler's eyes (readfirstlane).
+template <int ROWBYTES, int TILE_BYTES, int NW, typename RowAddr>
+__device__ __forceinline__ void tile_load_buffer(__amdgpu_buffer_rsrc_t rsrc, int soff, char* lds_tile,
+                                                 int wave, int lane, RowAddr rowaddr) {
+  constexpr int CPR = ROWBYTES / 16;
+  constexpr int RPB = 1024 / ROWBYTES;
+  constexpr int NBLK = TILE_BYTES / 1024;
+  static_assert(NBLK % NW == 0, "blocks of a tile are dealt evenly to the waves");
+  static_assert(NW % 4 == 0, "the chunk swizzle must not depend on which of its blocks a wave moves");
+  const int j = lane / CPR;
+  const int c = (lane % CPR) ^ swz<ROWBYTES>(wave * RPB + j);
+  const int voff = rowaddr(j) + c * 16;
+#pragma unroll
+  for (int n = 0; n < NBLK / NW; ++n) {
+    const int blk = wave + NW * n;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds_tile + blk * 1024),
+                                             16, voff, soff + rowaddr(blk * RPB), 0, 0);
+  }
+}
+
 // Wait until at most N of this wave's direct loads are outstanding (and all of
 // its LDS accesses are done), then workgroup barrier.  Written as one asm block:
 // the compiler's own barrier would wait for every outstanding direct load and

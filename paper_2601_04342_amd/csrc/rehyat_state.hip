@@ -44,7 +44,7 @@ state_kernel(StateArgs a) {
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform for the compiler too
   const int g = lane >> 5;
   const int r = lane & 31;
   const int i16 = lane & 15;
@@ -90,11 +90,12 @@ state_kernel(StateArgs a) {
   }
   auto contiguous = [](int R) { return R * (2 * D); };
   // tile `it` of K or V, rows at or beyond `valid` re-read the last valid row
-  auto issue_tile = [&](const char* gb, char* dst, int it, int valid) {
-    const char* src = gb + (int64_t)it * TB;
+  const __amdgpu_buffer_rsrc_t Kr = make_rsrc(Kb), Vr = make_rsrc(Vb);
+  auto issue_tile = [&](__amdgpu_buffer_rsrc_t rsrc, const char* gb, char* dst, int it, int valid) {
     if (valid >= 64) {
-      tile_load_direct<2 * D, TB, NW>(src, dst, wave, lane, contiguous);
+      tile_load_buffer<2 * D, TB, NW>(rsrc, it * TB, dst, wave, lane, contiguous);
     } else {
+      const char* src = gb + (int64_t)it * TB;
       auto clamped = [valid](int R) { return (R < valid ? R : valid - 1) * (2 * D); };
       tile_load_direct<2 * D, TB, NW>(src, dst, wave, lane, clamped);
     }
@@ -103,10 +104,10 @@ state_kernel(StateArgs a) {
   auto valid_of = [&](int it) { return it < n_full ? 64 : rem; };
 #pragma unroll
   for (int j = 0; j < HID / 64; ++j)
-    tile_load_direct<2 * D, TB, NW>(W1 + j * TB, W1s + j * TB, wave, lane, contiguous);
+    tile_load_buffer<2 * D, TB, NW>(make_rsrc(W1), j * TB, W1s + j * TB, wave, lane, contiguous);
   if (n_tiles > 0) {
-    issue_tile(Kb, Xs, 0, valid_of(0));
-    issue_tile(Vb, Vs, 0, valid_of(0));
+    issue_tile(Kr, Kb, Xs, 0, valid_of(0));
+    issue_tile(Vr, Vb, Vs, 0, valid_of(0));
   }
 
   // ---- per-lane LDS byte offsets ----------------------------------------------
@@ -172,7 +173,7 @@ state_kernel(StateArgs a) {
       }
     }
     wait_loads_and_barrier<0>();   // U complete; this tile's V has landed; X is free
-    if (it + 1 < n_tiles) issue_tile(Kb, Xs, it + 1, valid_of(it + 1));
+    if (it + 1 < n_tiles) issue_tile(Kr, Kb, Xs, it + 1, valid_of(it + 1));
     // ---- second half ---------------------------------------------------------------
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
@@ -210,7 +211,7 @@ state_kernel(StateArgs a) {
       }
     }
     wait_loads_and_barrier<0>();   // next K tile has landed; U and V are free
-    if (it + 1 < n_tiles) issue_tile(Vb, Vs, it + 1, valid_of(it + 1));
+    if (it + 1 < n_tiles) issue_tile(Vr, Vb, Vs, it + 1, valid_of(it + 1));
   };
 
   for (int it = 0; it < n_full; ++it) tile_step(std::false_type{}, it);
