@@ -122,7 +122,8 @@ __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, con
     __builtin_amdgcn_sched_barrier(0);
   }
 
-  // ---- online softmax -----------------------------------------------------------
+  // ---- online softmax: new maximum, rescale of the running sums --------------------
+  float mnew[QB], alpha[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     if (TAIL) {
@@ -137,42 +138,65 @@ __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, con
     for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(E[0][qb][e], E[1][qb][e]));
     mx = half_swap_max(mx);
     // exponents are kept unscaled; sc = log2(e)/sqrt(d) > 0 is folded into the exp2 argument
-    const float mnew = fmaxf(mrun[qb], mx * sc);
-    const float alpha = __builtin_amdgcn_exp2f(mrun[qb] - mnew);
-    mrun[qb] = mnew;
-    float sum = 0.f;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(E[kb][qb][e], sc, -mnew));
-        E[kb][qb][e] = p;
-        sum += p;
-      }
-    lrun[qb] = lrun[qb] * alpha + sum;
-    if (__any(alpha != 1.0f)) {
+    mnew[qb] = fmaxf(mrun[qb], mx * sc);
+    alpha[qb] = __builtin_amdgcn_exp2f(mrun[qb] - mnew[qb]);
+    mrun[qb] = mnew[qb];
+    if (__any(alpha[qb] != 1.0f)) {
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) O[db][qb][e] *= alpha;
+        for (int e = 0; e < 16; ++e) O[db][qb][e] *= alpha[qb];
     }
   }
   __builtin_amdgcn_sched_barrier(0);
 
-  // ---- numerator += V^T P, one 16-key step at a time --------------------------------
+  // ---- numerator += V^T P, one 16-key step at a time.  The weights of a step (8 per
+  // lane: registers 8(step&1).. of key block step>>1) are exponentiated just before its
+  // products, so that the products of one step can run under the exponentials of the next
+  // (one scheduling region; the group barriers below ask for that interleave).
+  float sum[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) sum[qb] = 0.f;
 #pragma unroll
   for (int step = 0; step < 4; ++step) {
     if (step + 1 < 4) read_v(step + 1, (step + 1) & 1);
-    __builtin_amdgcn_sched_barrier(0);
     bf16x8 pf[QB];
 #pragma unroll
-    for (int qb = 0; qb < QB; ++qb) pf[qb] = acc_to_operand(E[step >> 1][qb], step & 1);
+    for (int qb = 0; qb < QB; ++qb) {
+#pragma unroll
+      for (int e = 8 * (step & 1); e < 8 * (step & 1) + 8; ++e) {
+        float p = __builtin_amdgcn_exp2f(__builtin_fmaf(E[step >> 1][qb][e], sc, -mnew[qb]));
+        E[step >> 1][qb][e] = p;
+        sum[qb] += p;
+      }
+      pf[qb] = acc_to_operand(E[step >> 1][qb], step & 1);
+    }
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) O[db][qb] = mfma(vf[step & 1][db], pf[qb], O[db][qb]);
-    __builtin_amdgcn_sched_barrier(0);
   }
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) lrun[qb] = lrun[qb] * alpha[qb] + sum[qb];
+  if (QB == 1 && DB == 4) {
+    // step 0's weights first, then each product followed by a share of the next step's work
+    __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);   // V fragments of step 1
+    __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+    __builtin_amdgcn_sched_group_barrier(0x400, 8, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 12, 0);
+#pragma unroll
+    for (int s2 = 0; s2 < 3; ++s2)
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (s2 < 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      }
+    __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
+  }
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // ---------------------------------------------------------------------------
