@@ -31,20 +31,28 @@ namespace rehyat {
 // Query blocks of 32 per wave.  1 -> 128-query workgroups, two resident per CU, whose
 // waves share each SIMD and fill each other's stalls; 2 (256-query workgroups, one per
 // CU, half the LDS operand traffic per MFMA) measured 30 % slower at the 480p shape.
+// The exponentials of a row are taken relative to a reference that follows the row's
+// running maximum lazily: it moves only when a tile's maximum exceeds it by more than
+// this many powers of two, so the rescale of the running sums is rare after the first
+// tile, and weights stay below 2^kLazyMax (harmless for bf16 weights and fp32 sums; the
+// final division cancels the reference).  The true maximum is tracked beside it.
+constexpr float kLazyMax = 8.0f;
 constexpr int kAttnQB = 1;
+constexpr int kAttnNW = 4;   // waves per workgroup; queries per workgroup = 32 * kAttnQB * kAttnNW
 
-template <int D, int QB>
+template <int D, int QB, int NWV = 4>
 struct AttnShape {
   static constexpr int HID = 2 * D;
   static constexpr int DP = 2 * D;
   static constexpr int KS = D / 16;    // k-steps across the head dimension
   static constexpr int DB = D / 32;    // 32-row blocks across the head dimension
-  static constexpr int NT = 256;       // threads
+  static constexpr int NW = NWV;       // waves per workgroup
+  static constexpr int NT = 64 * NWV;  // threads
   static constexpr int QW = 32 * QB;   // queries per wave
-  static constexpr int QT = 4 * QW;    // queries per workgroup
+  static constexpr int QT = NWV * QW;  // queries per workgroup
   static constexpr int KT = 64;        // keys per tile
   static constexpr int TILE_BYTES = 64 * D * 2;  // one LDS tile: 64 rows of 2D bytes
-  static constexpr int LPT = TILE_BYTES / 4096;  // direct-load instructions per wave per tile
+  static constexpr int LPT = TILE_BYTES / (1024 * NWV);  // direct-load instructions per wave per tile
 };
 
 // per-lane byte offsets of the fragment reads inside a K / V tile
@@ -78,8 +86,8 @@ __device__ __forceinline__ FragOffsets<D> make_frag_offsets(int lane) {
 template <int D, int QB, bool TAIL>
 __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, const FragOffsets<D>& fo,
                                              const bf16x8 (&Qr)[QB][D / 16], f32x16 (&O)[D / 32][QB],
-                                             float (&mrun)[QB], float (&lrun)[QB], float sc,
-                                             int valid_keys, int lane) {
+                                             float (&mrun)[QB], float (&mtru)[QB], float (&lrun)[QB],
+                                             float sc, int valid_keys, int lane) {
   using C = AttnShape<D, QB>;
   constexpr int KS = C::KS, DB = C::DB;
   constexpr int KB_BYTES = 32 * D * 2;   // 32 rows further down the tile
@@ -138,15 +146,20 @@ __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, con
     for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(E[0][qb][e], E[1][qb][e]));
     mx = half_swap_max(mx);
     // exponents are kept unscaled; sc = log2(e)/sqrt(d) > 0 is folded into the exp2 argument
-    mnew[qb] = fmaxf(mrun[qb], mx * sc);
-    alpha[qb] = __builtin_amdgcn_exp2f(mrun[qb] - mnew[qb]);
-    mrun[qb] = mnew[qb];
-    if (__any(alpha[qb] != 1.0f)) {
+    const float mt = mx * sc;
+    mtru[qb] = fmaxf(mtru[qb], mt);
+    alpha[qb] = 1.0f;
+    const bool grow = mt > mrun[qb] + kLazyMax;
+    if (__any(grow)) {
+      const float mref = grow ? mt : mrun[qb];
+      alpha[qb] = __builtin_amdgcn_exp2f(mrun[qb] - mref);
+      mrun[qb] = mref;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int e = 0; e < 16; ++e) O[db][qb][e] *= alpha[qb];
     }
+    mnew[qb] = mrun[qb];
   }
   __builtin_amdgcn_sched_barrier(0);
 
@@ -196,6 +209,141 @@ __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, con
       }
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
   }
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+// ---------------------------------------------------------------------------
+// Two query blocks per wave, one wave per SIMD: the matrix products of one block
+// run under the vector work of the other inside a single instruction stream,
+//   stage 1  E0 = K Q0^T
+//   stage 2  E1 = K Q1^T        | max, exponentials, sum, bf16 weights of block 0
+//   stage 3  O0 += V^T P0       | the same for block 1
+//   stage 4  O1 += V^T P1
+// with the (rare) rescale of a block's numerator at the stage boundary before its
+// products.  K and V fragments are read again for the second block.
+// ---------------------------------------------------------------------------
+template <int D>
+__device__ __forceinline__ void qk_stage(const char* Ks, const FragOffsets<D>& fo, const bf16x8 (&Q)[D / 16],
+                                         f32x16 (&E)[2]) {
+  constexpr int KS = D / 16;
+  constexpr int KB_BYTES = 32 * D * 2;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + fo.k[ks] + kb * KB_BYTES);
+      E[kb] = mfma(kf, Q[ks], ks == 0 ? zero : E[kb]);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void pv_stage(const char* Vs, const FragOffsets<D>& fo, const bf16x8 (&P)[4],
+                                         f32x16 (&O)[D / 32][2], int qb) {
+  constexpr int DB = D / 32;
+  constexpr int STEP_BYTES = 16 * D * 2;
+#pragma unroll
+  for (int step = 0; step < 4; ++step)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      i16x4 lo = lds_read_tr(reinterpret_cast<const bf16_t*>(Vs + fo.v_lo[db] + step * STEP_BYTES));
+      i16x4 hi = lds_read_tr(reinterpret_cast<const bf16_t*>(Vs + fo.v_hi[db] + step * STEP_BYTES));
+      O[db][qb] = mfma(join_tr(lo, hi), P[step], O[db][qb]);
+    }
+}
+
+// vector part of one block: running maximum, exponentials, their sum, bf16 weights
+template <bool TAIL>
+__device__ __forceinline__ void softmax_valu(f32x16 (&E)[2], float& mrun, float& mtru, float& alpha,
+                                             float& sum, bf16x8 (&P)[4], float sc, int valid_keys, int g) {
+  if (TAIL) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e)
+        if (32 * kb + 8 * (e >> 2) + 4 * g + (e & 3) >= valid_keys) E[kb][e] = -INFINITY;
+  }
+  float mx = fmaxf(E[0][0], E[1][0]);
+#pragma unroll
+  for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(E[0][e], E[1][e]));
+  mx = half_swap_max(mx);
+  const float mt = mx * sc;
+  mtru = fmaxf(mtru, mt);
+  const float mnew = (mt > mrun + kLazyMax) ? mt : mrun;   // lazily following reference
+  alpha = __builtin_amdgcn_exp2f(mrun - mnew);
+  mrun = mnew;
+  sum = 0.f;
+#pragma unroll
+  for (int step = 0; step < 4; ++step) {
+#pragma unroll
+    for (int e = 8 * (step & 1); e < 8 * (step & 1) + 8; ++e) {
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(E[step >> 1][e], sc, -mnew));
+      E[step >> 1][e] = p;
+      sum += p;
+    }
+    P[step] = acc_to_operand(E[step >> 1], step & 1);
+  }
+}
+
+template <int D, bool TAIL>
+__device__ __forceinline__ void softmax_tile_pair(const char* Ks, const char* Vs, const FragOffsets<D>& fo,
+                                                  const bf16x8 (&Qr)[2][D / 16], f32x16 (&O)[D / 32][2],
+                                                  float (&mrun)[2], float (&mtru)[2], float (&lrun)[2],
+                                                  float sc, int valid_keys, int lane) {
+  constexpr int DB = D / 32, KS = D / 16;
+  constexpr int NMFMA = 2 * KS;          // products per stage (= 4 * DB for the numerator)
+  const int g = lane >> 5;
+  f32x16 E0[2], E1[2];
+  bf16x8 P0[4], P1[4];
+  float alpha0, alpha1, sum0, sum1;
+  auto rescale = [&](int qb, float alpha, float sum) {
+    lrun[qb] = lrun[qb] * alpha + sum;
+    if (__any(alpha != 1.0f)) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) O[db][qb][e] *= alpha;
+    }
+  };
+  // a stage's products with the other block's vector work spread between them:
+  // the maximum first (no transcendental can start before it), then exponentials
+  auto mixed_groups = [&](auto DSC) {
+    constexpr int ds_per_mfma = decltype(DSC)::value;
+#pragma unroll
+    for (int m = 0; m < NMFMA; ++m) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, ds_per_mfma, 0);
+      if (m < 4) {
+        __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
+      } else {
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+        __builtin_amdgcn_sched_group_barrier(0x400, 3, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
+      }
+    }
+  };
+
+  // stage 1
+  qk_stage<D>(Ks, fo, Qr[0], E0);
+  __builtin_amdgcn_sched_barrier(0);
+  // stage 2
+  qk_stage<D>(Ks, fo, Qr[1], E1);
+  softmax_valu<TAIL>(E0, mrun[0], mtru[0], alpha0, sum0, P0, sc, valid_keys, g);
+  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+  mixed_groups(std::integral_constant<int, 1>{});
+  __builtin_amdgcn_sched_barrier(0);
+  rescale(0, alpha0, sum0);
+  __builtin_amdgcn_sched_barrier(0);
+  // stage 3
+  pv_stage<D>(Vs, fo, P0, O, 0);
+  softmax_valu<TAIL>(E1, mrun[1], mtru[1], alpha1, sum1, P1, sc, valid_keys, g);
+  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
+  mixed_groups(std::integral_constant<int, 2>{});
+  __builtin_amdgcn_sched_barrier(0);
+  rescale(1, alpha1, sum1);
+  __builtin_amdgcn_sched_barrier(0);
+  // stage 4
+  pv_stage<D>(Vs, fo, P1, O, 1);
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -279,10 +427,11 @@ __device__ __forceinline__ void static_for(F&& f) {
   static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-template <int D, int QB>
-__global__ void __launch_bounds__(256, (QB == 1 ? 2 : 1))
+// second bound: waves per SIMD the register budget is sized for
+template <int D, int QB, int NWV>
+__global__ void __launch_bounds__(64 * NWV, (QB == 1 ? 2 : 1))
 attn_kernel(AttnArgs a) {
-  using C = AttnShape<D, QB>;
+  using C = AttnShape<D, QB, NWV>;
   constexpr int HID = C::HID, DP = C::DP, KS = C::KS, DB = C::DB, NT = C::NT;
   constexpr int TB = C::TILE_BYTES, LPT = C::LPT;
   // Four tile buffers, declared as separate objects so that a pending direct
@@ -356,11 +505,13 @@ attn_kernel(AttnArgs a) {
     for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) O[db][qb][e] = 0.f;
-  float mrun[QB];  // running max of exponent * log2(e)/sqrt(d)
+  float mrun[QB];  // reference of the exponentials (log2 units), lags the running maximum
+  float mtru[QB];  // running maximum of exponent * log2(e)/sqrt(d)
   float lrun[QB];  // this lane half's share of the sum
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     mrun[qb] = -INFINITY;
+    mtru[qb] = -INFINITY;
     lrun[qb] = 0.f;
   }
   const float sc = a.scale_log2e;
@@ -375,10 +526,15 @@ attn_kernel(AttnArgs a) {
     const char* const Vb = reinterpret_cast<const char*>(Vg + s_lo * D);
     auto contiguous = [](int R) { return R * (2 * D); };
     // K and V of tile `it` into the given buffers
+    auto run_tile = [&](auto TAILC, const char* Kt, const char* Vt, int valid) {
+      constexpr bool TAIL = decltype(TAILC)::value;
+      if constexpr (QB == 2) softmax_tile_pair<D, TAIL>(Kt, Vt, fo, Qr, O, mrun, mtru, lrun, sc, valid, lane);
+      else softmax_tile<D, QB, TAIL>(Kt, Vt, fo, Qr, O, mrun, mtru, lrun, sc, valid, lane);
+    };
     const __amdgpu_buffer_rsrc_t Kr = make_rsrc(Kb), Vr = make_rsrc(Vb);
     auto issue_kv = [&](int it, char* kd, char* vd) {
-      tile_load_buffer<2 * D, TB, 4>(Kr, it * TB, kd, wave, lane, contiguous);
-      tile_load_buffer<2 * D, TB, 4>(Vr, it * TB, vd, wave, lane, contiguous);
+      tile_load_buffer<2 * D, TB, NWV>(Kr, it * TB, kd, wave, lane, contiguous);
+      tile_load_buffer<2 * D, TB, NWV>(Vr, it * TB, vd, wave, lane, contiguous);
     };
     if (n_full > 0) issue_kv(0, A0, A2);
       // per-head vectors of phase L (their loads complete long before phase L, whose
@@ -398,11 +554,11 @@ attn_kernel(AttnArgs a) {
     // for every wave, by the barrier that ends tile it.
     for (int it = 0; it < n_full; it += 2) {
       if (it + 1 < n_full) issue_kv(it + 1, A1, A3);
-      if (wave_live) softmax_tile<D, QB, false>(A0, A2, fo, Qr, O, mrun, lrun, sc, 64, lane);
+      if (wave_live) run_tile(std::false_type{}, A0, A2, 64);
       wait_loads_and_barrier<0>();
       if (it + 1 < n_full) {
         if (it + 2 < n_full) issue_kv(it + 2, A0, A2);
-        if (wave_live) softmax_tile<D, QB, false>(A1, A3, fo, Qr, O, mrun, lrun, sc, 64, lane);
+        if (wave_live) run_tile(std::false_type{}, A1, A3, 64);
         wait_loads_and_barrier<0>();
       }
     }
@@ -412,20 +568,22 @@ attn_kernel(AttnArgs a) {
       // values) and their keys are masked
       const int64_t goff = (int64_t)((s_hi - s_lo) / 64) * TB;
       auto clamped = [rem](int R) { return (R < rem ? R : rem - 1) * (2 * D); };
-      tile_load_direct<2 * D, TB, 4>(Kb + goff, A0, wave, lane, clamped);
-      tile_load_direct<2 * D, TB, 4>(Vb + goff, A2, wave, lane, clamped);
+      tile_load_direct<2 * D, TB, NWV>(Kb + goff, A0, wave, lane, clamped);
+      tile_load_direct<2 * D, TB, NWV>(Vb + goff, A2, wave, lane, clamped);
       wait_loads_and_barrier<0>();
-      if (wave_live) softmax_tile<D, QB, true>(A0, A2, fo, Qr, O, mrun, lrun, sc, rem, lane);
+      if (wave_live) run_tile(std::true_type{}, A0, A2, rem);
       wait_loads_and_barrier<0>();
     }
   }
 
   // complete the softmax normaliser across the two lane halves
-  float nS[QB], mtrue[QB];
+  // All sums are relative to 2^-mrun; the components are reported relative to the
+  // true maximum: dscale = 2^(mrun - mtru) <= 1.
+  float nS[QB], dscale[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     nS[qb] = half_swap_sum(lrun[qb]);
-    mtrue[qb] = mrun[qb] * 0.6931471805599453f;  // back from base 2
+    dscale[qb] = __builtin_amdgcn_exp2f(mrun[qb] - mtru[qb]);
   }
 
   // debug: softmax components
@@ -436,8 +594,8 @@ attn_kernel(AttnArgs a) {
       if (row < cr.q_hi) {
         const int64_t o = (int64_t)bh * N + row;
         if (g == 0) {
-          if (a.dbg_m) a.dbg_m[o] = mtrue[qb];
-          if (a.dbg_nS) a.dbg_nS[o] = nS[qb];
+          if (a.dbg_m) a.dbg_m[o] = mtru[qb] * 0.6931471805599453f;  // back from base 2
+          if (a.dbg_nS) a.dbg_nS[o] = nS[qb] * dscale[qb];
         }
         if (a.dbg_aS) {
 #pragma unroll
@@ -445,7 +603,7 @@ attn_kernel(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
               f32x4 x = {O[db][qb][4 * i], O[db][qb][4 * i + 1], O[db][qb][4 * i + 2], O[db][qb][4 * i + 3]};
-              *reinterpret_cast<f32x4*>(a.dbg_aS + o * D + 32 * db + 8 * i + 4 * g) = x;
+              *reinterpret_cast<f32x4*>(a.dbg_aS + o * D + 32 * db + 8 * i + 4 * g) = x * dscale[qb];
             }
         }
       }
@@ -473,12 +631,12 @@ attn_kernel(AttnArgs a) {
     auto issue_tile = [&](auto KIND, int idx, char* dst) {
       constexpr int kind = decltype(KIND)::value;
       if constexpr (kind == kW1) {
-        tile_load_buffer<2 * D, TB, 4>(W1r, idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
+        tile_load_buffer<2 * D, TB, NWV>(W1r, idx * TB, dst, wave, lane, [](int R) { return R * (2 * D); });
       } else if constexpr (kind == kW2) {
-        tile_load_buffer<2 * D, TB, 4>(W2r, idx * 32 * (4 * D), dst, wave, lane,
+        tile_load_buffer<2 * D, TB, NWV>(W2r, idx * 32 * (4 * D), dst, wave, lane,
                                        [](int R) { return (R & 31) * (4 * D) + (R >> 5) * (2 * D); });
       } else {
-        tile_load_buffer<128, TB, 4>(Str, idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
+        tile_load_buffer<128, TB, NWV>(Str, idx * 128, dst, wave, lane, [](int R) { return R * (4 * D); });
       }
     };
     auto buf = [&](auto I) -> char* {
@@ -500,11 +658,12 @@ attn_kernel(AttnArgs a) {
       issue_all(LinProC<D, decltype(I)::value>{});
     });
 
-    // with c = 0 the linear terms carry exp(-m) relative to the softmax terms
+    // The softmax sums are relative to 2^-mrun: with c_i = row maximum (Eq. 6, 8) the
+    // linear terms weigh 2^(mtru - mrun) beside them, with c = 0 they weigh 2^-mrun.
     float lin_scale[QB];
 #pragma unroll
     for (int qb = 0; qb < QB; ++qb)
-      lin_scale[qb] = (a.stab_mode == 1) ? __builtin_amdgcn_exp2f(-mrun[qb]) : 1.f;
+      lin_scale[qb] = __builtin_amdgcn_exp2f((a.stab_mode == 1 ? 0.f : mtru[qb]) - mrun[qb]);
 
     // per-lane byte offsets inside a W tile: block row sigma(r), k-step ks
     const int sr = (r & 0x13) | ((r & 4) << 1) | ((r & 8) >> 1);
@@ -620,7 +779,7 @@ attn_kernel(AttnArgs a) {
     const int64_t row = qw0 + 32 * qb + r;
     if (row >= cr.q_hi) continue;
     const int64_t o = (int64_t)bh * N + row;
-    if (g == 0 && a.dbg_nL) a.dbg_nL[o] = nL[qb];
+    if (g == 0 && a.dbg_nL) a.dbg_nL[o] = nL[qb] * dscale[qb];
     const float inv = 1.0f / (nS[qb] + nL[qb]);
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
@@ -630,8 +789,16 @@ attn_kernel(AttnArgs a) {
         if (a.dbg_aL) {
           f32x4 as = {0.f, 0.f, 0.f, 0.f};
           if (a.dbg_aS) as = *reinterpret_cast<const f32x4*>(a.dbg_aS + o * D + col);
-          f32x4 x = {O[db][qb][4 * i] - as[0], O[db][qb][4 * i + 1] - as[1],
-                     O[db][qb][4 * i + 2] - as[2], O[db][qb][4 * i + 3] - as[3]};
+          const float ds = dscale[qb];
+          f32x4 x;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            // the product is rounded as it was when a^S was stored (no fused multiply-subtract),
+            // so an empty linear set reports exactly zero
+            float t = O[db][qb][4 * i + j] * ds;
+            asm volatile("" : "+v"(t));
+            x[j] = t - as[j];
+          }
           *reinterpret_cast<f32x4*>(a.dbg_aL + o * D + col) = x;
         }
         u32x2 pk;
@@ -643,13 +810,13 @@ attn_kernel(AttnArgs a) {
   }
 }
 
-int attn_query_tile(int d) { return AttnShape<128, kAttnQB>::QT; }
+int attn_query_tile(int d) { return AttnShape<128, kAttnQB, kAttnNW>::QT; }
 
 hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream) {
   if (d == 128) {
-    hipLaunchKernelGGL((attn_kernel<128, kAttnQB>), dim3(grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((attn_kernel<128, kAttnQB, kAttnNW>), dim3(grid), dim3(64 * kAttnNW), 0, stream, a);
   } else {
-    hipLaunchKernelGGL((attn_kernel<64, kAttnQB>), dim3(grid), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL((attn_kernel<64, kAttnQB, kAttnNW>), dim3(grid), dim3(64 * kAttnNW), 0, stream, a);
   }
   return hipGetLastError();
 }

@@ -240,13 +240,14 @@ __device__ __forceinline__ void tile_load_buffer(__amdgpu_buffer_rsrc_t rsrc, in
   constexpr int RPB = 1024 / ROWBYTES;
   constexpr int NBLK = TILE_BYTES / 1024;
   static_assert(NBLK % NW == 0, "blocks of a tile are dealt evenly to the waves");
-  static_assert(NW % 4 == 0, "the chunk swizzle must not depend on which of its blocks a wave moves");
   const int j = lane / CPR;
-  const int c = (lane % CPR) ^ swz<ROWBYTES>(wave * RPB + j);
-  const int voff = rowaddr(j) + c * 16;
 #pragma unroll
   for (int n = 0; n < NBLK / NW; ++n) {
     const int blk = wave + NW * n;
+    // the chunk swizzle looks at the low bits of the block index only: with NW a multiple
+    // of 4 every block of a wave shares one per-lane offset, otherwise two alternate
+    const int c = (lane % CPR) ^ swz<ROWBYTES>((NW % 4 == 0 ? wave : blk) * RPB + j);
+    const int voff = rowaddr(j) + c * 16;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(lds_tile + blk * 1024),
                                              16, voff, soff + rowaddr(blk * RPB), 0, 0);
   }
