@@ -28,15 +28,15 @@
 
 namespace rehyat {
 
-// Query blocks of 32 per wave.  1 -> 128-query workgroups, two resident per CU, whose
-// waves share each SIMD and fill each other's stalls; 2 (256-query workgroups, one per
-// CU, half the LDS operand traffic per MFMA) measured 30 % slower at the 480p shape.
 // The exponentials of a row are taken relative to a reference that follows the row's
 // running maximum lazily: it moves only when a tile's maximum exceeds it by more than
 // this many powers of two, so the rescale of the running sums is rare after the first
 // tile, and weights stay below 2^kLazyMax (harmless for bf16 weights and fp32 sums; the
 // final division cancels the reference).  The true maximum is tracked beside it.
 constexpr float kLazyMax = 8.0f;
+// Query blocks of 32 per wave.  1 -> 128-query workgroups, two resident per CU, whose
+// waves share each SIMD and fill each other's stalls; 2 (one wave per SIMD with twice the
+// registers, half the LDS operand traffic per MFMA) measured 30 % slower at the 480p shape.
 constexpr int kAttnQB = 1;
 constexpr int kAttnNW = 4;   // waves per workgroup; queries per workgroup = 32 * kAttnQB * kAttnNW
 
@@ -209,141 +209,6 @@ __device__ __forceinline__ void softmax_tile(const char* Ks, const char* Vs, con
       }
     __builtin_amdgcn_sched_group_barrier(0x008, 4, 0);
   }
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-// ---------------------------------------------------------------------------
-// Two query blocks per wave, one wave per SIMD: the matrix products of one block
-// run under the vector work of the other inside a single instruction stream,
-//   stage 1  E0 = K Q0^T
-//   stage 2  E1 = K Q1^T        | max, exponentials, sum, bf16 weights of block 0
-//   stage 3  O0 += V^T P0       | the same for block 1
-//   stage 4  O1 += V^T P1
-// with the (rare) rescale of a block's numerator at the stage boundary before its
-// products.  K and V fragments are read again for the second block.
-// ---------------------------------------------------------------------------
-template <int D>
-__device__ __forceinline__ void qk_stage(const char* Ks, const FragOffsets<D>& fo, const bf16x8 (&Q)[D / 16],
-                                         f32x16 (&E)[2]) {
-  constexpr int KS = D / 16;
-  constexpr int KB_BYTES = 32 * D * 2;
-  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
-      bf16x8 kf = *reinterpret_cast<const bf16x8*>(Ks + fo.k[ks] + kb * KB_BYTES);
-      E[kb] = mfma(kf, Q[ks], ks == 0 ? zero : E[kb]);
-    }
-}
-
-template <int D>
-__device__ __forceinline__ void pv_stage(const char* Vs, const FragOffsets<D>& fo, const bf16x8 (&P)[4],
-                                         f32x16 (&O)[D / 32][2], int qb) {
-  constexpr int DB = D / 32;
-  constexpr int STEP_BYTES = 16 * D * 2;
-#pragma unroll
-  for (int step = 0; step < 4; ++step)
-#pragma unroll
-    for (int db = 0; db < DB; ++db) {
-      i16x4 lo = lds_read_tr(reinterpret_cast<const bf16_t*>(Vs + fo.v_lo[db] + step * STEP_BYTES));
-      i16x4 hi = lds_read_tr(reinterpret_cast<const bf16_t*>(Vs + fo.v_hi[db] + step * STEP_BYTES));
-      O[db][qb] = mfma(join_tr(lo, hi), P[step], O[db][qb]);
-    }
-}
-
-// vector part of one block: running maximum, exponentials, their sum, bf16 weights
-template <bool TAIL>
-__device__ __forceinline__ void softmax_valu(f32x16 (&E)[2], float& mrun, float& mtru, float& alpha,
-                                             float& sum, bf16x8 (&P)[4], float sc, int valid_keys, int g) {
-  if (TAIL) {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e)
-        if (32 * kb + 8 * (e >> 2) + 4 * g + (e & 3) >= valid_keys) E[kb][e] = -INFINITY;
-  }
-  float mx = fmaxf(E[0][0], E[1][0]);
-#pragma unroll
-  for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(E[0][e], E[1][e]));
-  mx = half_swap_max(mx);
-  const float mt = mx * sc;
-  mtru = fmaxf(mtru, mt);
-  const float mnew = (mt > mrun + kLazyMax) ? mt : mrun;   // lazily following reference
-  alpha = __builtin_amdgcn_exp2f(mrun - mnew);
-  mrun = mnew;
-  sum = 0.f;
-#pragma unroll
-  for (int step = 0; step < 4; ++step) {
-#pragma unroll
-    for (int e = 8 * (step & 1); e < 8 * (step & 1) + 8; ++e) {
-      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(E[step >> 1][e], sc, -mnew));
-      E[step >> 1][e] = p;
-      sum += p;
-    }
-    P[step] = acc_to_operand(E[step >> 1], step & 1);
-  }
-}
-
-template <int D, bool TAIL>
-__device__ __forceinline__ void softmax_tile_pair(const char* Ks, const char* Vs, const FragOffsets<D>& fo,
-                                                  const bf16x8 (&Qr)[2][D / 16], f32x16 (&O)[D / 32][2],
-                                                  float (&mrun)[2], float (&mtru)[2], float (&lrun)[2],
-                                                  float sc, int valid_keys, int lane) {
-  constexpr int DB = D / 32, KS = D / 16;
-  constexpr int NMFMA = 2 * KS;          // products per stage (= 4 * DB for the numerator)
-  const int g = lane >> 5;
-  f32x16 E0[2], E1[2];
-  bf16x8 P0[4], P1[4];
-  float alpha0, alpha1, sum0, sum1;
-  auto rescale = [&](int qb, float alpha, float sum) {
-    lrun[qb] = lrun[qb] * alpha + sum;
-    if (__any(alpha != 1.0f)) {
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) O[db][qb][e] *= alpha;
-    }
-  };
-  // a stage's products with the other block's vector work spread between them:
-  // the maximum first (no transcendental can start before it), then exponentials
-  auto mixed_groups = [&](auto DSC) {
-    constexpr int ds_per_mfma = decltype(DSC)::value;
-#pragma unroll
-    for (int m = 0; m < NMFMA; ++m) {
-      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-      __builtin_amdgcn_sched_group_barrier(0x100, ds_per_mfma, 0);
-      if (m < 4) {
-        __builtin_amdgcn_sched_group_barrier(0x002, 9, 0);
-      } else {
-        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-        __builtin_amdgcn_sched_group_barrier(0x400, 3, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);
-      }
-    }
-  };
-
-  // stage 1
-  qk_stage<D>(Ks, fo, Qr[0], E0);
-  __builtin_amdgcn_sched_barrier(0);
-  // stage 2
-  qk_stage<D>(Ks, fo, Qr[1], E1);
-  softmax_valu<TAIL>(E0, mrun[0], mtru[0], alpha0, sum0, P0, sc, valid_keys, g);
-  __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-  mixed_groups(std::integral_constant<int, 1>{});
-  __builtin_amdgcn_sched_barrier(0);
-  rescale(0, alpha0, sum0);
-  __builtin_amdgcn_sched_barrier(0);
-  // stage 3
-  pv_stage<D>(Vs, fo, P0, O, 0);
-  softmax_valu<TAIL>(E1, mrun[1], mtru[1], alpha1, sum1, P1, sc, valid_keys, g);
-  __builtin_amdgcn_sched_group_barrier(0x100, 8, 0);
-  mixed_groups(std::integral_constant<int, 2>{});
-  __builtin_amdgcn_sched_barrier(0);
-  rescale(1, alpha1, sum1);
-  __builtin_amdgcn_sched_barrier(0);
-  // stage 4
-  pv_stage<D>(Vs, fo, P1, O, 1);
   __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -528,8 +393,7 @@ attn_kernel(AttnArgs a) {
     // K and V of tile `it` into the given buffers
     auto run_tile = [&](auto TAILC, const char* Kt, const char* Vt, int valid) {
       constexpr bool TAIL = decltype(TAILC)::value;
-      if constexpr (QB == 2) softmax_tile_pair<D, TAIL>(Kt, Vt, fo, Qr, O, mrun, mtru, lrun, sc, valid, lane);
-      else softmax_tile<D, QB, TAIL>(Kt, Vt, fo, Qr, O, mrun, mtru, lrun, sc, valid, lane);
+      softmax_tile<D, QB, TAIL>(Kt, Vt, fo, Qr, O, mrun, mtru, lrun, sc, valid, lane);
     };
     const __amdgpu_buffer_rsrc_t Kr = make_rsrc(Kb), Vr = make_rsrc(Vb);
     auto issue_kv = [&](int it, char* kd, char* vd) {

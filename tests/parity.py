@@ -36,15 +36,17 @@ def oracle_inputs(q, k, v, phi, heads=None, batch=None):
             {n: p.double().numpy() for n, p in phi.items()})
 
 
-def compare(out, comps, ref, stab=0, rows=None, label=""):
+def compare(out, comps, ref, stab=0, rows=None, label="", out_scale=1.0):
     """out/comps: GPU results already restricted to the oracle's (b, h) subset,
-    full token axis; ref: oracle Components on `rows` (None = all)."""
+    full token axis; ref: oracle Components on `rows` (None = all).  `out_scale`
+    widens the absolute bars on the output for cases whose outputs exceed O(1): the
+    bf16 output alone is off by up to 2^-9 of its magnitude."""
     sel = slice(None) if rows is None else rows
     o = out.float().cpu().double().numpy()[:, :, sel]
     assert np.isfinite(o).all(), label
     err = np.abs(o - ref.out)
-    assert err.max() <= OUT_MAX_ABS, (label, "out max-abs", err.max())
-    assert err.mean() <= OUT_MEAN_ABS, (label, "out mean-abs", err.mean())
+    assert err.max() <= OUT_MAX_ABS * out_scale, (label, "out max-abs", err.max())
+    assert err.mean() <= OUT_MEAN_ABS * out_scale, (label, "out mean-abs", err.mean())
     if comps is None:
         return err.max(), err.mean()
     c = {n: t.cpu().double().numpy()[:, :, sel] for n, t in comps.items()}
@@ -59,12 +61,12 @@ def compare(out, comps, ref, stab=0, rows=None, label=""):
         nL, aL = ref.nL * sc, ref.aL * sc[..., None]
     assert (np.abs(c["nS"] - nS) <= NS_REL * nS).all(), (label, "nS")
     assert (np.abs(c["nL"] - nL) <= NL_REL * nL + 1e-30).all(), (label, "nL")
-    assert np.abs(c["aS"] / c["nS"][..., None] - aS / nS[..., None]).max() <= AVG_ABS, (label, "aS")
+    assert np.abs(c["aS"] / c["nS"][..., None] - aS / nS[..., None]).max() <= AVG_ABS * out_scale, (label, "aS")
     has_l = nL > 0
     if has_l.any():
         g = c["aL"][has_l] / c["nL"][has_l][..., None]
         r = aL[has_l] / nL[has_l][..., None]
-        assert np.abs(g - r).max() <= AVG_ABS, (label, "aL")
+        assert np.abs(g - r).max() <= AVG_ABS * out_scale, (label, "aL")
     assert (c["nL"][~has_l] == 0).all() and (c["aL"][~has_l] == 0).all(), (label, "empty linear set")
     return err.max(), err.mean()
 

@@ -87,6 +87,28 @@ def test_bidirectional_small_shapes_match_oracle(case):
           f"{parity.linear_share(ref, stab):.2f}", flush=True)
 
 
+@pytest.mark.parametrize("scale,stab", [(6.0, 0), (6.0, 1), (0.05, 0)])
+def test_wide_and_narrow_score_ranges(scale, stab):
+    """Scores far apart (row maxima keep growing from tile to tile by more and by less
+    than the kernel's rescale threshold) and nearly equal scores."""
+    B, H, T, HW, d = 1, 2, 3, 450, 128
+    q, k, v = synth.make_qkv(B, H, T * HW, d, seed=17)
+    q = synth.round_bf16(q * scale)
+    if stab == 1:   # keep exp(score) itself inside fp32 when nothing is subtracted
+        q = synth.round_bf16(q * 0.5)
+    phi = synth.make_phi(H, d, seed=18, gain=3.0)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    out, comps = binding.forward(dq, dk, dv, dphi, T, HW, 1, overlap=1, stab_mode=stab, debug=True)
+    torch.cuda.synchronize()
+    ref = cref.forward(*parity.oracle_inputs(q, k, v, phi), T, HW, 1, overlap=1, stab=stab)
+    spread = float(ref.m.max() - ref.m.min())
+    # peaked rows return nearly a single v row, |y| up to about 4: the absolute bars,
+    # set for O(1) outputs, scale with the largest output (bf16 keeps 8 bits)
+    mag = max(1.0, float(np.abs(ref.out).max()))
+    print(f"   row maxima span {spread:.1f} nats, largest |y| {mag:.2f}", flush=True)
+    parity.compare(out, comps, ref, stab=stab, label=f"score scale {scale} stab {stab}", out_scale=mag)
+
+
 def test_zero_phi_is_block_diagonal_softmax():
     """phi = 0 isolates the softmax kernel: chunk-local softmax attention."""
     B, H, T, HW, d = 1, 2, 3, 200, 128
