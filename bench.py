@@ -18,10 +18,10 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # HBM bytes per launch of the fused attention kernel on the wan480p workload, from
-# two rocprofv3 --pmc runs: 2.0 x FETCH_SIZE (172,961 KiB) + 1.0 x WRITE_SIZE
+# two rocprofv3 --pmc runs: 2.0 x FETCH_SIZE (167,878 KiB) + 1.0 x WRITE_SIZE
 # (98,280 KiB), the factors being those a 1 GiB device copy shows in the same runs
 # (profiles/wan480p_hbm_traffic_pmc.md).  Other workloads report null.
-ATTN_TRAFFIC_BYTES = {"wan480p": 454863744}
+ATTN_TRAFFIC_BYTES = {"wan480p": 444453760}
 
 
 def algorithmic_flops(w, overlap=0, causal=True):
@@ -169,7 +169,7 @@ def main():
         "kernel_ms": kern_ms,
         "kernel_launches_per_step": {kk: n / args.steps for kk, (_, n) in prof.items()},
         "workspace_bytes": binding.workspace_bytes(w.B, w.H, w.d),
-        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128, 1>", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128, 1, 4>", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": ATTN_TRAFFIC_BYTES.get(w.name) if args.mode == "forward" else None},
