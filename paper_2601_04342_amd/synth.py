@@ -44,6 +44,8 @@ WORKLOADS = {
     # chunk sizes of the T_c ablation
     "p320_t21_c3": Workload("p320_t21_c3", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=3),
     "p320_t41_c3": Workload("p320_t41_c3", B=1, H=12, d=128, T=41, HW=20 * 30, chunk=3),
+    # a long generation: 34 chunks, more than one window of chunk-state slots
+    "p320_t101_c3": Workload("p320_t101_c3", B=1, H=12, d=128, T=101, HW=20 * 30, chunk=3),
     "p320_t21_c5": Workload("p320_t21_c5", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=5),
     "p320_t21_c7": Workload("p320_t21_c7", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=7),
 }

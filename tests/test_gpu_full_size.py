@@ -88,6 +88,14 @@ def test_bidirectional_full_size(name, overlap):
     check_workload(name, heads=[6], overlap=overlap, debug=True, gain=0.35, causal=False)
 
 
+def test_long_generation_several_state_windows():
+    """101 latent frames at the 320x480 shape (34 chunks of T_c = 3, T_o = 1): the chunk
+    states are produced in two windows with the carry between them, causal and
+    bidirectional."""
+    check_workload("p320_t101_c3", heads=[8], overlap=1, debug=True, gain=0.5)
+    check_workload("p320_t101_c3", heads=[3], overlap=1, debug=True, gain=0.5, causal=False)
+
+
 def test_long_video_flat_workspace():
     """Doubling the latent frames leaves the workspace untouched (section 3.3,
     point 3): the same caller-owned buffer serves T=21 and T=41, the library
