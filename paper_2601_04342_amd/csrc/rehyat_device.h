@@ -86,10 +86,6 @@ __device__ __forceinline__ bf16x8 acc_to_operand(const f32x16& c, int s) {
   return __builtin_bit_cast(bf16x8, p);
 }
 
-__device__ __forceinline__ bf16x8 lds_read_frag(const bf16_t* p) {
-  return *reinterpret_cast<const bf16x8*>(p);
-}
-
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each group of 16 lanes,
 // lane i passes the address of 4 consecutive bf16 of row (i / 4) at column
 // group (i % 4) of a 4 x 16 block and receives column i of that block, rows
@@ -97,84 +93,6 @@ __device__ __forceinline__ bf16x8 lds_read_frag(const bf16_t* p) {
 __device__ __forceinline__ i16x4 lds_read_tr(const bf16_t* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
       (__attribute__((address_space(3))) i16x4*)(p));
-}
-
-// A operand taken from a row-major [token][feature] LDS tile as its transpose:
-// rows of the operand are 32 features starting at `col0`, the eight k-values of
-// lane half g are tokens row0 + {4g..4g+3, 8+4g..8+4g+3} (the order produced by
-// acc_to_operand).  `ld` is the tile's row stride in elements.
-__device__ __forceinline__ bf16x8 lds_read_frag_transposed(const bf16_t* tile, int ld,
-                                                         int row0, int col0, int lane) {
-  const int g = lane >> 5;
-  const int r = lane & 31;
-  const int i = lane & 15;
-  const bf16_t* p = tile + (row0 + 4 * g + (i >> 2)) * ld + col0 + 16 * (r >> 4) + 4 * (i & 3);
-  i16x4 lo = lds_read_tr(p);
-  i16x4 hi = lds_read_tr(p + 8 * ld);
-  typedef __attribute__((__vector_size__(8 * sizeof(short)))) short i16x8;
-  i16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  return __builtin_bit_cast(bf16x8, v);
-}
-
-// ---------------------------------------------------------------------------
-// Cooperative global -> LDS staging of a [ROWS][COLS] bf16 tile by NT threads,
-// split into a load half (global -> registers, issued early) and a store half
-// (registers -> LDS, after the previous tile's readers have passed a barrier).
-// Rows at or beyond `valid_rows` are filled with zeros.  With SWAP the two
-// middle quads of every 16-column group are exchanged on the way in.
-// ---------------------------------------------------------------------------
-template <int ROWS, int COLS, int NT>
-struct TileRegs {
-  static constexpr int VPR = COLS / 8;               // 16-byte vectors per row
-  static constexpr int NV = (ROWS * VPR + NT - 1) / NT;  // vectors per thread
-  u32x4 v[NV];
-};
-
-template <int ROWS, int COLS, int NT, bool CHECK>
-__device__ __forceinline__ void tile_load(TileRegs<ROWS, COLS, NT>& regs, const bf16_t* src,
-                                          int64_t src_ld, int valid_rows, int tid) {
-  constexpr int VPR = COLS / 8;
-#pragma unroll
-  for (int n = 0; n < TileRegs<ROWS, COLS, NT>::NV; ++n) {
-    const int vi = tid + n * NT;
-    const int row = vi / VPR;
-    const int cv = vi % VPR;
-    u32x4 x = {0u, 0u, 0u, 0u};
-    constexpr bool exact = (ROWS * VPR) % NT == 0;  // no thread runs past the tile
-    if ((exact || row < ROWS) && (!CHECK || row < valid_rows))
-      x = *reinterpret_cast<const u32x4*>(src + (int64_t)row * src_ld + cv * 8);
-    regs.v[n] = x;
-  }
-}
-
-template <int ROWS, int COLS, int NT, bool SWAP>
-__device__ __forceinline__ void tile_store(const TileRegs<ROWS, COLS, NT>& regs, bf16_t* dst,
-                                           int dst_ld, int tid) {
-  constexpr int VPR = COLS / 8;
-#pragma unroll
-  for (int n = 0; n < TileRegs<ROWS, COLS, NT>::NV; ++n) {
-    const int vi = tid + n * NT;
-    const int row = vi / VPR;
-    const int cv = vi % VPR;
-    if (row < ROWS) {
-      bf16_t* p = dst + row * dst_ld + cv * 8;
-      if (!SWAP) {
-        *reinterpret_cast<u32x4*>(p) = regs.v[n];
-      } else {
-        // columns 16m+0..7 (cv even): quad 0 stays, quad 1 goes to position 8
-        // columns 16m+8..15 (cv odd): quad 2 goes to position 4, quad 3 stays
-        u32x2 a = {regs.v[n][0], regs.v[n][1]};
-        u32x2 b = {regs.v[n][2], regs.v[n][3]};
-        if ((cv & 1) == 0) {
-          *reinterpret_cast<u32x2*>(p) = a;
-          *reinterpret_cast<u32x2*>(p + 8) = b;
-        } else {
-          *reinterpret_cast<u32x2*>(p - 4) = a;
-          *reinterpret_cast<u32x2*>(p + 4) = b;
-        }
-      }
-    }
-  }
 }
 
 // ---------------------------------------------------------------------------
