@@ -118,7 +118,9 @@ int rehyat_set_workspace(void *dev_ptr, size_t bytes);
  *   T   latent frames, HW tokens per frame, chunk = T_c frames per chunk
  *       (a short last chunk when T % chunk != 0; chunk >= T is one chunk,
  *       i.e. plain softmax attention, Eq. 2)
- * Supported: d in {64, 128}; B*H*N*d < 2^62; N < 2^31.
+ * Supported: d in {64, 128}; B*H <= 65535; N < 2^31; one softmax window
+ * ((chunk + overlap) * HW tokens) below 2^31 bytes per head; anything beyond
+ * returns REHYAT_E_SHAPE.
  */
 int rehyat_forward(const void *q, const void *k, const void *v,
                    const rehyat_phi_params *phi_params, void *out, int B, int H,

@@ -399,6 +399,16 @@ int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_
   if (B < 1 || H < 1 || T < 1 || HW < 1 || d < 1 || chunk < 1 || overlap < 0) return REHYAT_E_SHAPE;
   if ((int64_t)T * HW >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
   if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
+  {
+    // one launch covers up to 32 chunks: its workgroup count must fit an int
+    const int64_t cf = chunk < T ? chunk : T;
+    const int64_t tiles = (cf * HW + 63) / 64;
+    if ((int64_t)B * H * kStateSlots * tiles >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+    // tile offsets inside one softmax window or state segment are 32-bit
+    int64_t wf = (int64_t)chunk + overlap;
+    if (wf > T) wf = T;
+    if (wf * HW * d * 2 >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  }
   if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
   int rc = check_phi(phi, d);
   if (rc != REHYAT_OK) return rc;
@@ -485,6 +495,8 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   if (B < 1 || H < 1 || d < 1 || n_q < 1 || n_win < 1 || n_absorb < 0) return REHYAT_E_SHAPE;
   if (n_absorb > n_win) return REHYAT_E_SHAPE;
   if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
+  if ((int64_t)B * H * ((n_q + 63) / 64) >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  if ((int64_t)n_win * d * 2 >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;   // 32-bit tile offsets
   if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
   int rc = check_phi(phi, d);
   if (rc != REHYAT_OK) return rc;

@@ -93,6 +93,9 @@ def test_forward_argument_validation_without_gpu():
                 (1, 2, 4, 0, 64, 1), (1, 2, 4, 8, 64, 0), (1, 2, 4, 8, 0, 1),
                 (1, 2, 70000, 70000, 64, 1)):
         assert fwd(1, 1, 1, P(ok), 1, *bad, None) == binding.E_SHAPE, bad
+    # one softmax window of 2^31 bytes or more per head; more workgroups than an int counts
+    assert fwd(1, 1, 1, P(ok), 1, 1, 2, 64, 1 << 18, 128, 64, None) == binding.E_SHAPE
+    assert fwd(1, 1, 1, P(ok), 1, 60000, 1, 4, 1 << 22, 128, 1, None) == binding.E_SHAPE
     assert fwd(1, 1, 1, P(ok), 1, 1, 2, 4, 8, 32, 1, None) == binding.E_UNSUPPORTED
     assert fwd(1, 1, 1, P(_phi(hidden=64)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
     assert fwd(1, 1, 1, P(_phi(degree=4)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
