@@ -169,7 +169,7 @@ def main():
         "kernel_ms": kern_ms,
         "kernel_launches_per_step": {kk: n / args.steps for kk, (_, n) in prof.items()},
         "workspace_bytes": binding.workspace_bytes(w.B, w.H, w.d),
-        "roofline": {"bound": "mfma", "kernel": "attn_kernel<128, 1, 4>", "achieved": achieved,
+        "roofline": {"bound": "mfma", "kernel": f"attn_kernel<{w.d}, 1, 4>", "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS,
                      "traffic": ATTN_TRAFFIC_BYTES.get(w.name) if args.mode == "forward" else None},

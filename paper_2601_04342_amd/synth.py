@@ -39,6 +39,9 @@ WORKLOADS = {
     "wan480p_cfg_c3": Workload("wan480p_cfg_c3", B=2, H=12, d=128, T=21, HW=30 * 52, chunk=3),
     "wan480p_long": Workload("wan480p_long", B=1, H=12, d=128, T=41, HW=30 * 52, chunk=1),
     "wan720p": Workload("wan720p", B=1, H=12, d=128, T=21, HW=45 * 80, chunk=1, rms_norm=False),
+    # the other supported head width at full length (not a shape of the paper: same bytes
+    # per token as wan480p, twice the heads)
+    "wide480p_d64": Workload("wide480p_d64", B=1, H=24, d=64, T=21, HW=30 * 52, chunk=1),
     # 320x480 generation (20 x 30 latent tokens per frame), the shape of the paper's
     # on-device tables (section 4.2): 21 to 41 latent frames, T_c = 3, and the larger
     # chunk sizes of the T_c ablation

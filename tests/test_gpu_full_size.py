@@ -88,6 +88,13 @@ def test_bidirectional_full_size(name, overlap):
     check_workload(name, heads=[6], overlap=overlap, debug=True, gain=0.35, causal=False)
 
 
+def test_head_width_64_full_length():
+    """d = 64 at the 480p token count: the narrower tile shapes and the linear-phase
+    schedule of that width, causal with components and bidirectional."""
+    check_workload("wide480p_d64", heads=[0, 23], debug=True, gain=0.5)
+    check_workload("wide480p_d64", heads=[11], overlap=1, gain=0.5, causal=False)
+
+
 def test_long_generation_several_state_windows():
     """101 latent frames at the 320x480 shape (34 chunks of T_c = 3, T_o = 1): the chunk
     states are produced in two windows with the carry between them, causal and
