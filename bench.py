@@ -5,10 +5,17 @@ One step = one call of rehyat_forward (chunk-state kernel, prefix pass, fused
 softmax / read-out / merge kernel) on the Wan2.1-1.3B 480p single-layer shape
 (B=1, H=12, d=128, 21 latent frames x 30x52 tokens = 32,760 tokens, chunk = 1
 frame), inputs resident in HBM.  Prints ONE JSON line.
+
+Two passes of --steps steps each: the first, with the library's per-kernel events
+off, gives the step time (median of per-step HIP event intervals on the launch
+stream; the wall-clock mean over the same region is reported beside it); the second,
+with them on, gives each kernel's average launch duration, from which the roofline
+figure of the dominant kernel is computed.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -17,18 +24,19 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-# HBM bytes per launch of the fused attention kernel on the wan480p workload, from
-# two rocprofv3 --pmc runs: 2.0 x FETCH_SIZE (167,878 KiB) + 1.0 x WRITE_SIZE
-# (98,280 KiB), the factors being those a 1 GiB device copy shows in the same runs
-# (profiles/wan480p_hbm_traffic_pmc.md).  Other workloads report null.
-ATTN_TRAFFIC_BYTES = {"wan480p": 444453760}
+# HBM bytes per launch of the fused attention kernel, from two rocprofv3 --pmc runs per
+# workload (FETCH_SIZE, then WRITE_SIZE; scaled by what a plain 1 GiB device copy reads on
+# the same counters in the same runs: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0), keyed by workload
+# and valid for the library version they were measured on (profiles/*_hbm_traffic_pmc.md).
+# Anything else reports null.
+ATTN_TRAFFIC = {}
 
 
-def algorithmic_flops(w, overlap=0, causal=True):
+def algorithmic_flops(w, chunk, overlap=0, causal=True):
     """Work the method itself requires (no padding, no unused last-chunk state,
     no phi_q / read-out for chunks whose linear set is empty)."""
     from paper_2601_04342_amd import binding
-    plan = binding.chunk_plan(w.T, w.HW, w.chunk, overlap).tolist()
+    plan = binding.chunk_plan(w.T, w.HW, chunk, overlap).tolist()
     BH, d, h, Dp = w.B * w.H, w.d, 2 * w.d, 2 * w.d
     softmax = 4 * d * BH * sum((r[1] - r[0]) * (r[3] - r[2]) for r in plan)
     phi_tok = 2 * (d * h + h * Dp)                      # one map, one token
@@ -47,19 +55,26 @@ def algorithmic_flops(w, overlap=0, causal=True):
                 attn_kernel=softmax + phi_q + readout, state_kernel=phi_k + state)
 
 
-def cpu_baseline(w, q, k, v, phi, heads):
-    """The fp64 oracle, as it stands, on `heads` heads of the same workload."""
+def cpu_baseline(w, chunk, q, k, v, phi, heads, gpu_out):
+    """The fp64 oracle, as it stands, on `heads` heads of the same workload, timed; its
+    output is then compared with what the GPU produced in the timed configuration."""
+    import numpy as np
     from oracle import cref
     qs, ks, vs = (x[:, :heads].double().numpy() for x in (q, k, v))
     ps = {n: p[:heads].double().numpy() for n, p in phi.items()}
     t0 = time.perf_counter()
-    cref.forward(qs, ks, vs, ps, w.T, w.HW, w.chunk)
+    ref = cref.forward(qs, ks, vs, ps, w.T, w.HW, chunk)
     dt = time.perf_counter() - t0
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": w.B * w.N * (heads / w.H) / dt, "unit": "tokens/s", "cores": threads,
+    base = {"value": w.B * w.N * (heads / w.H) / dt, "unit": "tokens/s", "cores": threads,
             "kind": "oracle", "seconds": round(dt, 3),
             "sample": f"{heads} of {w.H} heads, all {w.N} tokens, fp64 C oracle (OpenMP); "
                       "value = layer-equivalent tokens/s"}
+    err = np.abs(gpu_out[:, :heads].float().cpu().double().numpy() - ref.out)
+    parity = {"max_abs": float(err.max()), "mean_abs": float(err.mean()),
+              "linear_share": float((ref.nL / (ref.nS + ref.nL)).mean()),
+              "elements": int(err.size), "against": "oracle, every element of the sampled heads"}
+    return base, parity
 
 
 def main():
@@ -70,10 +85,12 @@ def main():
     ap.add_argument("--workload", default="wan480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=12)
-    ap.add_argument("--mode", choices=("forward", "bidirectional", "stream"), default="forward",
+    ap.add_argument("--mode", choices=("forward", "bidirectional", "stream", "fullsoftmax"),
+                    default="forward",
                     help="forward: rehyat_forward (the headline path); bidirectional: "
                          "rehyat_forward_ex(causal=0); stream: one rehyat_step per chunk with "
-                         "caller-owned state and window")
+                         "caller-owned state and window; fullsoftmax: rehyat_forward with one "
+                         "chunk covering all frames (plain softmax attention, Eq. 2) on the same inputs")
     ap.add_argument("--overlap", type=int, default=0, help="T_o (bidirectional and stream modes)")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="after the timed steps also run one plain device-to-device copy of this "
@@ -92,21 +109,22 @@ def main():
         sys.exit(1)
     binding.library()   # fails loudly if the HIP library is not built
     w = synth.WORKLOADS[args.workload]
+    chunk = w.T if args.mode == "fullsoftmax" else w.chunk
     q, k, v, phi = synth.make_workload(w)
     dq, dk, dv = (x.to("cuda", torch.bfloat16).contiguous() for x in (q, k, v))
     dphi = binding.phi_to_device(phi)
-    out = torch.empty_like(dq)
+    out = torch.full_like(dq, float("nan"))
     causal = args.mode != "bidirectional"
-    overlap = args.overlap if args.mode != "forward" else 0
-    if args.mode == "forward":
-        step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, out=out, plain=True)
+    overlap = args.overlap if args.mode in ("bidirectional", "stream") else 0
+    if args.mode in ("forward", "fullsoftmax"):
+        step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, chunk, out=out, plain=True)
     elif args.mode == "bidirectional":
-        step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, out=out,
+        step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, chunk, out=out,
                                        overlap=overlap, causal=False)
     else:
         # the caller's side of chunk-by-chunk generation: per chunk its queries, its K/V
         # window and the number of tokens that leave the window, prepared outside the timing
-        plan = binding.chunk_plan(w.T, w.HW, w.chunk, overlap).tolist()
+        plan = binding.chunk_plan(w.T, w.HW, chunk, overlap).tolist()
         pieces = []
         for t, (q_lo, q_hi, s_lo, s_hi, _) in enumerate(plan):
             n_absorb = plan[t + 1][2] - s_lo if t + 1 < len(plan) else 0
@@ -125,15 +143,30 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    binding.profile_enable(True)
+
+    # ---- pass 1: step time, per-kernel events off --------------------------------
+    binding.profile_enable(False)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(args.steps):
+        step()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps)]
+    ms = statistics.median(per_step)
+
+    # ---- pass 2: kernel durations, per-kernel events on ----------------------------
+    binding.profile_enable(True)
+    torch.cuda.synchronize()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
     prof = binding.profile_read()
     binding.profile_enable(False)
+
     if args.mode == "stream":
         out = torch.cat([p[3] for p in pieces], dim=2)
     assert torch.isfinite(out.float()).all()
@@ -145,39 +178,42 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    ms = dt * 1e3 / args.steps
-    fl = algorithmic_flops(w, overlap, causal)
+    fl = algorithmic_flops(w, chunk, overlap, causal)
     kern_ms = {kk: (tot / n if n else None) for kk, (tot, n) in prof.items()}
     # all launches of the attention kernel in one step share the step's algorithmic work
     attn_ms = prof["attn"][0] / args.steps
     achieved = fl["attn_kernel"] / (attn_ms * 1e-3) / 1e12
+    traffic = ATTN_TRAFFIC.get((w.name, args.mode, binding.version()))
     res = {
         "metric": "hybrid-attn tokens/s per layer @Wan2.1-480p shape; TFLOP/s and % MFMA peak",
         "value": w.B * w.N / (ms * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "ms_per_step_wall_mean": wall_ms,
+        "ms_per_step_min_max": [min(per_step), max(per_step)],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} T={w.T} HW={w.HW} "
-                               f"N={w.N} chunk={w.chunk} overlap={overlap} "
+                               f"N={w.N} chunk={chunk} overlap={overlap} "
                                f"{'causal' if causal else 'bidirectional'} row-max"
-                               + (", one rehyat_step per chunk" if args.mode == "stream" else ""),
+                               + (", one rehyat_step per chunk" if args.mode == "stream" else "")
+                               + (", one chunk = plain softmax attention" if args.mode == "fullsoftmax" else ""),
                    "phi": "hidden=D'=2d, degree 2, ReLU, N(0,0.02) seed 1",
-                   "qkv": "N(0,1) seed 0, q,k RMS-normalised, bf16"},
+                   "qkv": "N(0,1) seed 0, bf16" + (", q,k RMS-normalised" if w.rms_norm else "")},
         "tflops": fl["total"] / (ms * 1e-3) / 1e12,
         "pct_mfma_peak": 100.0 * fl["total"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
         "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in fl.items()},
         "kernel_ms": kern_ms,
         "kernel_launches_per_step": {kk: n / args.steps for kk, (_, n) in prof.items()},
         "workspace_bytes": binding.workspace_bytes(w.B, w.H, w.d),
-        "roofline": {"bound": "mfma", "kernel": f"attn_kernel<{w.d}, 1, 4>", "achieved": achieved,
+        "library_version": binding.version(),
+        "roofline": {"bound": "mfma", "kernel": binding.attn_kernel_name(w.d), "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": ATTN_TRAFFIC_BYTES.get(w.name) if args.mode == "forward" else None},
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
         "state_kernel_tflops": (fl["state_kernel"] / (prof["state"][0] / args.steps * 1e-3) / 1e12
                                 if prof["state"][1] else None),
     }
-    if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, q, k, v, phi, args.cpu_heads)
+    if not args.no_cpu_baseline and args.mode == "forward":
+        res["cpu_baseline"], res["parity"] = cpu_baseline(w, chunk, q, k, v, phi, args.cpu_heads, out)
     print(json.dumps(res))
 
 

@@ -22,8 +22,16 @@
  *    unless stated otherwise.  Token index inside a head is
  *    frame * HW + position, frame-major, as in section 3.2's flattening of the
  *    (T, H, W) latent.
+ *  - Alignment: q, k, v, out and the phi weight matrices must be 16-byte
+ *    aligned (rows are moved 16 bytes at a time), fp32 tensors 4-byte aligned,
+ *    a workspace 256-byte aligned; otherwise REHYAT_E_SHAPE (REHYAT_E_WORKSPACE
+ *    for a workspace).
  *  - Results are deterministic: repeated calls give bit-identical outputs.
- *  - Calls that share a workspace must be ordered on one stream.
+ *  - Calls that share a workspace must be ordered on one stream.  Entry points
+ *    without a workspace argument share the one the library holds and are
+ *    serialised by an internal lock; rehyat_forward_ws takes its workspace per
+ *    call and may run concurrently with any other call on any stream as long as
+ *    the workspaces differ.
  */
 #ifndef REHYAT_H_
 #define REHYAT_H_
@@ -37,7 +45,7 @@ extern "C" {
 
 #define REHYAT_OK 0
 #define REHYAT_E_NULL (-1)        /* a required pointer is NULL */
-#define REHYAT_E_SHAPE (-2)       /* a size is non-positive or inconsistent */
+#define REHYAT_E_SHAPE (-2)       /* a size is non-positive or inconsistent, or a pointer misaligned */
 #define REHYAT_E_UNSUPPORTED (-3) /* valid in the paper, not built here */
 #define REHYAT_E_WORKSPACE (-4)   /* workspace missing, too small or misaligned */
 #define REHYAT_E_HIP (-5)         /* a HIP runtime call failed */
@@ -103,10 +111,16 @@ int rehyat_chunk_plan(int T, int HW, int chunk, int overlap, int64_t *table,
 size_t rehyat_workspace_bytes(int B, int H, int d, int dprime);
 
 /*
- * Give the library a caller-owned DEVICE workspace (256-byte aligned).  If no
- * workspace has been set, or the one set is too small for a call, the library
- * allocates its own with hipMalloc on first need and keeps it until
- * rehyat_shutdown().  Pass (NULL, 0) to return to library-owned memory.
+ * Give the library a caller-owned DEVICE workspace (256-byte aligned) for the
+ * entry points that take none.  It is never replaced behind the caller's back:
+ * a call that needs more than `bytes` returns REHYAT_E_WORKSPACE and launches
+ * nothing.  Pass (NULL, 0) to return to library-owned memory: the library then
+ * allocates with hipMalloc on first need, grows (free + allocate) when a later
+ * call needs more, and keeps the buffer until rehyat_shutdown().  Growth
+ * invalidates HIP graphs captured from earlier calls; while `stream` is being
+ * captured the library neither allocates nor frees and returns
+ * REHYAT_E_WORKSPACE instead -- size the workspace (one eager call, or
+ * rehyat_set_workspace) before capturing.
  */
 int rehyat_set_workspace(void *dev_ptr, size_t bytes);
 
@@ -143,6 +157,22 @@ int rehyat_forward_ex(const void *q, const void *k, const void *v,
                       int H, int T, int HW, int d, int chunk, int overlap,
                       int causal, int stab_mode, const rehyat_debug_out *debug,
                       void *stream);
+
+/*
+ * rehyat_forward_ex with the workspace passed per call (no debug outputs):
+ * `workspace` is a DEVICE pointer, 256-byte aligned, of at least
+ * rehyat_workspace_bytes(B, H, d, dprime) bytes, used only for the duration of
+ * the enqueued work and not retained.  No library state is read or written, so
+ * two streams, two layers or the two halves of a guidance pair can be in flight
+ * at once, each with its own workspace (section 3.3 gives every sequence its
+ * own running state).  Errors as rehyat_forward_ex, plus REHYAT_E_NULL
+ * (workspace NULL) and REHYAT_E_WORKSPACE (misaligned or too small).
+ */
+int rehyat_forward_ws(const void *q, const void *k, const void *v,
+                      const rehyat_phi_params *phi_params, void *out, int B,
+                      int H, int T, int HW, int d, int chunk, int overlap,
+                      int causal, int stab_mode, void *workspace,
+                      size_t workspace_bytes, void *stream);
 
 /*
  * One step of the chunk-wise RNN (section 3.3, Eq. 14-18) for generation chunk by
@@ -207,6 +237,10 @@ const char *rehyat_status_string(int code);
 
 /* Library version: major * 10000 + minor * 100 + patch. */
 int rehyat_version(void);
+
+/* Name of the fused attention kernel instance launched for head width d, as a
+ * profiler's kernel trace shows it ("" for an unsupported d). */
+const char *rehyat_attn_kernel_name(int d);
 
 /* Text of the last HIP error seen by this library ("" if none). */
 const char *rehyat_last_hip_error(void);

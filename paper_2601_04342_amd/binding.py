@@ -19,8 +19,10 @@ STAB_ROWMAX, STAB_NONE = 0, 1
 
 # every symbol include/rehyat.h declares
 EXPORTS = ("rehyat_chunk_plan", "rehyat_workspace_bytes", "rehyat_set_workspace",
-           "rehyat_forward", "rehyat_forward_ex", "rehyat_step", "rehyat_state", "rehyat_shutdown",
+           "rehyat_forward", "rehyat_forward_ex", "rehyat_forward_ws",
+           "rehyat_step", "rehyat_state", "rehyat_shutdown",
            "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error",
+           "rehyat_attn_kernel_name",
            "rehyat_profile_enable", "rehyat_profile_read")
 
 
@@ -71,6 +73,10 @@ def _load():
     lib.rehyat_forward_ex.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp,
                                       ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                       ctypes.POINTER(DebugOut), vp]
+    lib.rehyat_forward_ws.restype = ci
+    lib.rehyat_forward_ws.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp,
+                                      ci, ci, ci, ci, ci, ci, ci, ci, ci,
+                                      vp, ctypes.c_size_t, vp]
     lib.rehyat_step.restype = ci
     lib.rehyat_step.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp, vp, vp,
                                 ci, ci, ci, ci, ci, ci, ci, vp]
@@ -85,6 +91,8 @@ def _load():
     lib.rehyat_version.argtypes = []
     lib.rehyat_last_hip_error.restype = ctypes.c_char_p
     lib.rehyat_last_hip_error.argtypes = []
+    lib.rehyat_attn_kernel_name.restype = ctypes.c_char_p
+    lib.rehyat_attn_kernel_name.argtypes = [ci]
     lib.rehyat_profile_enable.restype = ci
     lib.rehyat_profile_enable.argtypes = [ci]
     lib.rehyat_profile_read.restype = ci
@@ -100,6 +108,10 @@ def library():
 
 def version():
     return _load().rehyat_version()
+
+
+def attn_kernel_name(d):
+    return _load().rehyat_attn_kernel_name(d).decode()
 
 
 def status_string(code):
@@ -202,13 +214,14 @@ def _check_qkv(q, k, v):
 
 
 def forward(q, k, v, phi, T, HW, chunk, out=None, overlap=0, causal=True,
-            stab_mode=STAB_ROWMAX, debug=False, stream=None, plain=False):
+            stab_mode=STAB_ROWMAX, debug=False, stream=None, plain=False, workspace=None):
     """Hybrid attention forward.  q, k, v: CUDA bf16 [B, H, T*HW, d].
 
     Returns ``out`` (bf16, same shape), or ``(out, components)`` with
     ``debug=True`` where components is a dict of fp32 tensors m, nS, aS, nL, aL.
     ``plain=True`` calls ``rehyat_forward`` (no extra knobs) instead of
-    ``rehyat_forward_ex``.
+    ``rehyat_forward_ex``; ``workspace`` (a CUDA byte tensor) calls
+    ``rehyat_forward_ws``.
     """
     lib = _load()
     _check_qkv(q, k, v)
@@ -227,6 +240,14 @@ def forward(q, k, v, phi, T, HW, chunk, out=None, overlap=0, causal=True,
                                 out.data_ptr(), B, H, T, HW, d, chunk, sp)
         if rc != OK:
             raise RehyatError(rc, "rehyat_forward")
+        return out
+    if workspace is not None:
+        rc = lib.rehyat_forward_ws(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(p),
+                                   out.data_ptr(), B, H, T, HW, d, chunk, overlap,
+                                   int(bool(causal)), stab_mode, workspace.data_ptr(),
+                                   workspace.numel() * workspace.element_size(), sp)
+        if rc != OK:
+            raise RehyatError(rc, "rehyat_forward_ws")
         return out
     comps, dbg = None, None
     if debug:

@@ -15,8 +15,13 @@ namespace {
 
 using namespace rehyat;
 
-constexpr int kPartialSlots = 64;  // (segment, piece) partial sums per (b, h) in flight
-constexpr int kStateSlots = 32;    // chunk states per (b, h) in flight = window length
+// Slot counts of a workspace: how many (segment, piece) partial sums and how many chunk
+// states per (b, h) can be in flight; the window of chunks processed between two carries
+// is min(partial / nsplit, state).  Every kernel takes both as arguments.
+struct Slots {
+  int partial, state;
+};
+constexpr Slots kSlots{64, 32};  // workspaces sized by rehyat_workspace_bytes
 constexpr int kMaxSplit = 8;
 constexpr int kCUs = 256;
 
@@ -34,7 +39,8 @@ int hip_fail(hipError_t e, const char* what) {
   return REHYAT_E_HIP;
 }
 
-// optional per-kernel timing with HIP events on the caller's stream
+// optional per-kernel timing with HIP events on the caller's stream (calls that use the
+// library-held workspace only: those are serialised by g_mu)
 constexpr int kProfKinds = 3;  // state, prefix, attention
 constexpr int kProfMaxPairs = 4096;
 struct Profiler {
@@ -49,8 +55,8 @@ Profiler g_prof;
 struct ProfScope {
   int slot = -1;
   hipStream_t st;
-  ProfScope(int kind, hipStream_t s) : st(s) {
-    if (!g_prof.on || g_prof.used >= kProfMaxPairs) return;
+  ProfScope(bool enabled, int kind, hipStream_t s) : st(s) {
+    if (!enabled || !g_prof.on || g_prof.used >= kProfMaxPairs) return;
     if (g_prof.used >= g_prof.created) {
       if (hipEventCreate(&g_prof.beg[g_prof.created]) != hipSuccess) return;
       if (hipEventCreate(&g_prof.end[g_prof.created]) != hipSuccess) return;
@@ -71,41 +77,55 @@ struct WsLayout {
   size_t partial, state_s, state_z, carry, total;
 };
 
-WsLayout ws_layout(int B, int H, int d, int dp) {
+WsLayout ws_layout(int B, int H, int d, int dp, Slots sl) {
   const size_t BH = (size_t)B * H;
   const size_t elems = (size_t)d * dp + dp;
   WsLayout L;
   size_t off = 0;
   L.partial = off;
-  off += align256(BH * kPartialSlots * elems * sizeof(float));
+  off += align256(BH * sl.partial * elems * sizeof(float));
   L.state_s = off;
-  off += align256(BH * kStateSlots * (size_t)d * dp * sizeof(bf16_t));
+  off += align256(BH * sl.state * (size_t)d * dp * sizeof(bf16_t));
   L.state_z = off;
-  off += align256(BH * kStateSlots * (size_t)dp * sizeof(float));
+  off += align256(BH * sl.state * (size_t)dp * sizeof(float));
   L.carry = off;
   off += align256(BH * elems * sizeof(float));
   L.total = off;
   return L;
 }
 
+// Where one call's kernels find their device memory and stream.
+struct Ctx {
+  char* ws;
+  WsLayout L;
+  Slots sl;
+  hipStream_t st;
+  bool prof;  // record per-kernel events (library-held workspace only)
+};
+
 bool supported_dims(int d, int dp) { return (d == 64 || d == 128) && dp == 2 * d; }
 
-int ensure_workspace(size_t need, char** base) {
+// The library-held workspace (caller-set or library-owned), at least `need` bytes.  A
+// caller-set buffer is never replaced; a library-owned one is allocated or grown here
+// unless `st` is capturing (an allocation would break the capture, and a free would leave
+// earlier graphs pointing at released memory).
+int ensure_workspace(size_t need, hipStream_t st, char** base) {
   if (g_ws.ptr && g_ws.bytes >= need) {
     *base = (char*)g_ws.ptr;
     return REHYAT_OK;
   }
-  if (g_ws.ptr && !g_ws.owned) {
-    // a caller-owned workspace that is too small is replaced by a library-owned one
-    g_ws = Workspace();
-  }
-  if (g_ws.ptr && g_ws.owned) {
-    hipError_t e = hipFree(g_ws.ptr);
+  if (g_ws.ptr && !g_ws.owned) return REHYAT_E_WORKSPACE;  // caller's buffer is too small
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  hipError_t e = hipStreamIsCapturing(st, &cap);
+  if (e != hipSuccess) return hip_fail(e, "hipStreamIsCapturing");
+  if (cap != hipStreamCaptureStatusNone) return REHYAT_E_WORKSPACE;
+  if (g_ws.ptr) {
+    e = hipFree(g_ws.ptr);
     g_ws = Workspace();
     if (e != hipSuccess) return hip_fail(e, "hipFree(workspace)");
   }
   void* p = nullptr;
-  hipError_t e = hipMalloc(&p, need);
+  e = hipMalloc(&p, need);
   if (e != hipSuccess) return hip_fail(e, "hipMalloc(workspace)");
   g_ws.ptr = p;
   g_ws.bytes = need;
@@ -113,6 +133,9 @@ int ensure_workspace(size_t need, char** base) {
   *base = (char*)p;
   return REHYAT_OK;
 }
+
+bool aligned16(const void* p) { return (((uintptr_t)p) & 15) == 0; }
+bool aligned4(const void* p) { return (((uintptr_t)p) & 3) == 0; }
 
 int check_phi(const rehyat_phi_params* p, int d) {
   if (!p) return REHYAT_E_NULL;
@@ -122,17 +145,22 @@ int check_phi(const rehyat_phi_params* p, int d) {
   if (p->dprime % p->degree) return REHYAT_E_SHAPE;
   if (p->hidden != 2 * d || p->dprime != 2 * d || p->degree != 2 || p->act != 0)
     return REHYAT_E_UNSUPPORTED;
+  // weight rows are fetched 16 bytes at a time, biases as single floats
+  if (!aligned16(p->w1_q) || !aligned16(p->w2_q) || !aligned16(p->w1_k) || !aligned16(p->w2_k))
+    return REHYAT_E_SHAPE;
+  if (!aligned4(p->b1_q) || !aligned4(p->b2_q) || !aligned4(p->b1_k) || !aligned4(p->b2_k))
+    return REHYAT_E_SHAPE;
   return REHYAT_OK;
 }
 
 // pieces per segment: more workgroups when (b, h, segment) alone cannot fill the chip
-int choose_nsplit(int BH, int n_seg_total) {
+int choose_nsplit(int BH, int n_seg_total, Slots sl) {
   if (n_seg_total < 1) return 1;
   int best = 1;
   double best_cost = 1e30;
-  for (int ns = 1; ns <= kMaxSplit; ++ns) {
-    int win = kPartialSlots / ns;
-    if (win > kStateSlots) win = kStateSlots;
+  for (int ns = 1; ns <= kMaxSplit && ns <= sl.partial; ++ns) {
+    int win = sl.partial / ns;
+    if (win > sl.state) win = sl.state;
     const int segs = n_seg_total < win ? n_seg_total : win;
     const int windows = (n_seg_total + win - 1) / win;
     const long wgs = (long)BH * segs * ns;
@@ -147,9 +175,9 @@ int choose_nsplit(int BH, int n_seg_total) {
   return best;
 }
 
-int launch_state_window(const void* k, const void* v, const rehyat_phi_params* phi, char* ws,
-                        const WsLayout& L, int B, int H, int T, int HW, int d, int chunk, int overlap,
-                        int chunk0, int n_seg, int nsplit, hipStream_t stream) {
+int launch_state_window(const Ctx& c, const void* k, const void* v, const rehyat_phi_params* phi,
+                        int B, int H, int T, int HW, int d, int chunk, int overlap, int chunk0,
+                        int n_seg, int nsplit) {
   StateArgs s;
   s.k = (const bf16_t*)k;
   s.v = (const bf16_t*)v;
@@ -157,7 +185,7 @@ int launch_state_window(const void* k, const void* v, const rehyat_phi_params* p
   s.b1_k = (const float*)phi->b1_k;
   s.w2_k = (const bf16_t*)phi->w2_k;
   s.b2_k = (const float*)phi->b2_k;
-  s.partial = (float*)(ws + L.partial);
+  s.partial = (float*)(c.ws + c.L.partial);
   s.H = H;
   s.T = T;
   s.HW = HW;
@@ -166,43 +194,43 @@ int launch_state_window(const void* k, const void* v, const rehyat_phi_params* p
   s.chunk0 = chunk0;
   s.n_seg = n_seg;
   s.nsplit = nsplit;
-  s.partial_slots = kPartialSlots;
+  s.partial_slots = c.sl.partial;
   s.n_items = B * H * n_seg * nsplit;
   s.items_per_xcd = (s.n_items + 7) / 8;
   s.kv_bh_stride = (int64_t)T * HW * d;
   s.step_n = 0;
-  ProfScope prof(0, stream);
-  hipError_t e = launch_state(s, d, s.items_per_xcd * 8, stream);
+  ProfScope prof(c.prof, 0, c.st);
+  hipError_t e = launch_state(s, d, s.items_per_xcd * 8, c.st);
   if (e != hipSuccess) return hip_fail(e, "state kernel launch");
   return REHYAT_OK;
 }
 
-int launch_prefix_window(char* ws, const WsLayout& L, int B, int H, int d, int dp, int n_chunks,
-                         int n_seg, int nsplit, bool first, hipStream_t stream) {
+int launch_prefix_window(const Ctx& c, int B, int H, int d, int dp, int n_chunks, int n_seg,
+                         int nsplit, bool first) {
   PrefixArgs p;
-  p.partial = (const float*)(ws + L.partial);
-  p.carry = (float*)(ws + L.carry);
-  p.state_s = (bf16_t*)(ws + L.state_s);
-  p.state_z = (float*)(ws + L.state_z);
+  p.partial = (const float*)(c.ws + c.L.partial);
+  p.carry = (float*)(c.ws + c.L.carry);
+  p.state_s = (bf16_t*)(c.ws + c.L.state_s);
+  p.state_z = (float*)(c.ws + c.L.state_z);
   p.BH = B * H;
   p.n_chunks = n_chunks;
   p.n_seg = n_seg;
   p.nsplit = nsplit;
-  p.partial_slots = kPartialSlots;
-  p.state_slots = kStateSlots;
+  p.partial_slots = c.sl.partial;
+  p.state_slots = c.sl.state;
   p.first_window = first ? 1 : 0;
   p.elems = d * dp + dp;
   p.s_elems = d * dp;
-  ProfScope prof(1, stream);
-  hipError_t e = launch_prefix(p, stream);
+  ProfScope prof(c.prof, 1, c.st);
+  hipError_t e = launch_prefix(p, c.st);
   if (e != hipSuccess) return hip_fail(e, "prefix kernel launch");
   return REHYAT_OK;
 }
 
-int launch_attn_window(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
-                       void* out, const rehyat_debug_out* debug, char* ws, const WsLayout& L, int B,
-                       int H, int T, int HW, int d, int chunk, int overlap, int c0, int n_chunks,
-                       int qtiles, int stab_mode, bool bidir, hipStream_t st) {
+int launch_attn_window(const Ctx& c, const void* q, const void* k, const void* v,
+                       const rehyat_phi_params* phi, void* out, const rehyat_debug_out* debug,
+                       int B, int H, int T, int HW, int d, int chunk, int overlap, int c0,
+                       int n_chunks, int qtiles, int stab_mode, bool bidir) {
   AttnArgs a;
   a.q = (const bf16_t*)q;
   a.k = (const bf16_t*)k;
@@ -212,8 +240,8 @@ int launch_attn_window(const void* q, const void* k, const void* v, const rehyat
   a.b1_q = (const float*)phi->b1_q;
   a.w2_q = (const bf16_t*)phi->w2_q;
   a.b2_q = (const float*)phi->b2_q;
-  a.state_s = (const bf16_t*)(ws + L.state_s);
-  a.state_z = (const float*)(ws + L.state_z);
+  a.state_s = (const bf16_t*)(c.ws + c.L.state_s);
+  a.state_z = (const float*)(c.ws + c.L.state_z);
   a.dbg_m = debug ? debug->m : nullptr;
   a.dbg_nS = debug ? debug->nS : nullptr;
   a.dbg_aS = debug ? debug->aS : nullptr;
@@ -228,7 +256,7 @@ int launch_attn_window(const void* q, const void* k, const void* v, const rehyat
   a.chunk0 = c0;
   a.n_win_chunks = n_chunks;
   a.qtiles = qtiles;
-  a.state_slots = kStateSlots;
+  a.state_slots = c.sl.state;
   a.stab_mode = stab_mode;
   a.n_items = B * H * n_chunks * qtiles;
   a.items_per_xcd = (a.n_items + 7) / 8;
@@ -237,8 +265,8 @@ int launch_attn_window(const void* q, const void* k, const void* v, const rehyat
   a.all_linear = bidir ? 1 : 0;
   hipError_t e;
   {
-    ProfScope prof(2, st);
-    e = launch_attn(a, d, a.items_per_xcd * 8, st);
+    ProfScope prof(c.prof, 2, c.st);
+    e = launch_attn(a, d, a.items_per_xcd * 8, c.st);
   }
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
   return REHYAT_OK;
@@ -247,30 +275,29 @@ int launch_attn_window(const void* q, const void* k, const void* v, const rehyat
 // Bidirectional sets (Eq. 11-12): the linear part of chunk t covers every token outside
 // its softmax window.  Per-frame sums F(f) of phi_k(k) v^T come from the chunk-state kernel
 // run with one-frame segments; state(t) = sum_f F(f) - sum_{f in window t} F(f).
-int forward_bidirectional(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
-                          void* out, const rehyat_debug_out* debug, char* ws, const WsLayout& L,
+int forward_bidirectional(const Ctx& c, const void* q, const void* k, const void* v,
+                          const rehyat_phi_params* phi, void* out, const rehyat_debug_out* debug,
                           int B, int H, int T, int HW, int d, int dp, int chunk, int overlap,
-                          int stab_mode, hipStream_t st) {
+                          int stab_mode) {
   const int nc = num_chunks(T, chunk);
-  const int chunk_frames = chunk < T ? chunk : T;
   const int qtile = attn_query_tile(d);
-  const int qtiles = (int)(((int64_t)chunk_frames * HW + qtile - 1) / qtile);
+  const int qtiles = (int)(((int64_t)chunk * HW + qtile - 1) / qtile);
   if (nc == 1)  // the window is the whole sequence: plain softmax attention
-    return launch_attn_window(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, chunk, overlap, 0, 1,
-                              qtiles, stab_mode, false, st);
-  int win_frames = chunk + overlap;  // frames one window can span
+    return launch_attn_window(c, q, k, v, phi, out, debug, B, H, T, HW, d, chunk, overlap, 0, 1,
+                              qtiles, stab_mode, false);
+  int win_frames = chunk + overlap;  // frames one window can span (both are <= T here)
   if (win_frames > T) win_frames = T;
-  if (win_frames > kPartialSlots) return REHYAT_E_UNSUPPORTED;
-  int nsplit = choose_nsplit(B * H, T);
-  while (nsplit > 1 && kPartialSlots / nsplit < win_frames) --nsplit;
-  const int fwin = kPartialSlots / nsplit;  // frames whose sums fit the partial slots
+  if (win_frames > c.sl.partial) return REHYAT_E_UNSUPPORTED;
+  int nsplit = choose_nsplit(B * H, T, c.sl);
+  while (nsplit > 1 && c.sl.partial / nsplit < win_frames) --nsplit;
+  const int fwin = c.sl.partial / nsplit;  // frames whose sums fit the partial slots
 
   // pass 1: total over all frames, left in the carry
   for (int f0 = 0; f0 < T; f0 += fwin) {
     const int n = (T - f0 < fwin) ? T - f0 : fwin;
-    int rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, 1, 0, f0, n, nsplit, st);
+    int rc = launch_state_window(c, k, v, phi, B, H, T, HW, d, 1, 0, f0, n, nsplit);
     if (rc != REHYAT_OK) return rc;
-    rc = launch_prefix_window(ws, L, B, H, d, dp, /*n_chunks=*/0, /*n_seg=*/n, nsplit, f0 == 0, st);
+    rc = launch_prefix_window(c, B, H, d, dp, /*n_chunks=*/0, /*n_seg=*/n, nsplit, f0 == 0);
     if (rc != REHYAT_OK) return rc;
   }
   const bool resident = T <= fwin;  // every F(f) is still in the partial slots
@@ -278,7 +305,7 @@ int forward_bidirectional(const void* q, const void* k, const void* v, const reh
   // pass 2: windows of chunks whose frames fit the partial slots together
   int cw = (fwin - overlap) / chunk;
   if (cw < 1) cw = 1;
-  if (cw > kStateSlots) cw = kStateSlots;
+  if (cw > c.sl.state) cw = c.sl.state;
   for (int c0 = 0; c0 < nc; c0 += cw) {
     const int c1 = (c0 + cw < nc) ? c0 + cw : nc;
     int F0 = c0 * chunk - overlap;
@@ -286,14 +313,14 @@ int forward_bidirectional(const void* q, const void* k, const void* v, const reh
     int F1 = c1 * chunk;
     if (F1 > T) F1 = T;
     if (!resident) {
-      int rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, 1, 0, F0, F1 - F0, nsplit, st);
+      int rc = launch_state_window(c, k, v, phi, B, H, T, HW, d, 1, 0, F0, F1 - F0, nsplit);
       if (rc != REHYAT_OK) return rc;
     }
     BidirArgs b;
-    b.partial = (const float*)(ws + L.partial);
-    b.total = (const float*)(ws + L.carry);
-    b.state_s = (bf16_t*)(ws + L.state_s);
-    b.state_z = (float*)(ws + L.state_z);
+    b.partial = (const float*)(c.ws + c.L.partial);
+    b.total = (const float*)(c.ws + c.L.carry);
+    b.state_s = (bf16_t*)(c.ws + c.L.state_s);
+    b.state_z = (float*)(c.ws + c.L.state_z);
     b.BH = B * H;
     b.T = T;
     b.chunk = chunk;
@@ -302,18 +329,84 @@ int forward_bidirectional(const void* q, const void* k, const void* v, const reh
     b.n_chunks = c1 - c0;
     b.frame0 = resident ? 0 : F0;
     b.nsplit = nsplit;
-    b.partial_slots = kPartialSlots;
-    b.state_slots = kStateSlots;
+    b.partial_slots = c.sl.partial;
+    b.state_slots = c.sl.state;
     b.elems = d * dp + dp;
     b.s_elems = d * dp;
     hipError_t e;
     {
-      ProfScope prof(1, st);
-      e = launch_bidir_state(b, st);
+      ProfScope prof(c.prof, 1, c.st);
+      e = launch_bidir_state(b, c.st);
     }
     if (e != hipSuccess) return hip_fail(e, "bidirectional state kernel launch");
-    int rc = launch_attn_window(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, chunk, overlap, c0,
-                                c1 - c0, qtiles, stab_mode, true, st);
+    int rc = launch_attn_window(c, q, k, v, phi, out, debug, B, H, T, HW, d, chunk, overlap, c0,
+                                c1 - c0, qtiles, stab_mode, true);
+    if (rc != REHYAT_OK) return rc;
+  }
+  return REHYAT_OK;
+}
+
+// Argument checks shared by every forward entry point.  On success chunk and overlap are
+// clamped to T (a chunk or an overlap longer than the video acts like T), so that no later
+// sum of them can leave the range of int.
+int validate_forward(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                     const void* out, int B, int H, int T, int HW, int d, int* chunk, int* overlap,
+                     int causal, int stab_mode) {
+  if (!q || !k || !v || !out) return REHYAT_E_NULL;
+  if (B < 1 || H < 1 || T < 1 || HW < 1 || d < 1 || *chunk < 1 || *overlap < 0) return REHYAT_E_SHAPE;
+  if ((int64_t)T * HW >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
+  if (*chunk > T) *chunk = T;
+  if (*overlap > T) *overlap = T;
+  {
+    // one launch covers up to 32 chunks: its workgroup count must fit an int
+    const int64_t tiles = ((int64_t)*chunk * HW + 63) / 64;
+    if ((int64_t)B * H * kSlots.state * tiles >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+    // tile offsets inside one softmax window or state segment are 32-bit
+    int64_t wf = (int64_t)*chunk + *overlap;
+    if (wf > T) wf = T;
+    if (wf * HW * d * 2 >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  }
+  if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
+  int rc = check_phi(phi, d);
+  if (rc != REHYAT_OK) return rc;
+  if (stab_mode != REHYAT_STAB_ROWMAX && stab_mode != REHYAT_STAB_NONE) return REHYAT_E_SHAPE;
+  if (causal != 0 && causal != 1) return REHYAT_E_SHAPE;
+  // rows are fetched and stored 16 bytes at a time
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(out)) return REHYAT_E_SHAPE;
+  return REHYAT_OK;
+}
+
+// The kernels of one forward call on validated arguments.
+int forward_core(const Ctx& c, const void* q, const void* k, const void* v,
+                 const rehyat_phi_params* phi, void* out, const rehyat_debug_out* debug, int B,
+                 int H, int T, int HW, int d, int chunk, int overlap, int causal, int stab_mode) {
+  const int dp = phi->dprime;
+  if (causal == 0)
+    return forward_bidirectional(c, q, k, v, phi, out, debug, B, H, T, HW, d, dp, chunk, overlap,
+                                 stab_mode);
+  const int nc = num_chunks(T, chunk);
+  const int nsplit = choose_nsplit(B * H, nc - 1, c.sl);
+  int win = c.sl.partial / nsplit;
+  if (win > c.sl.state) win = c.sl.state;
+  const int qtile = attn_query_tile(d);
+  const int qtiles = (int)(((int64_t)chunk * HW + qtile - 1) / qtile);
+
+  for (int c0 = 0; c0 < nc; c0 += win) {
+    const int c1 = (c0 + win < nc) ? c0 + win : nc;
+    const int n_chunks = c1 - c0;
+    const int n_seg = (c1 < nc) ? n_chunks : n_chunks - 1;
+    int rc;
+    if (n_seg > 0) {
+      rc = launch_state_window(c, k, v, phi, B, H, T, HW, d, chunk, overlap, c0, n_seg, nsplit);
+      if (rc != REHYAT_OK) return rc;
+    }
+    if (nc > 1) {
+      rc = launch_prefix_window(c, B, H, d, dp, n_chunks, n_seg, nsplit, c0 == 0);
+      if (rc != REHYAT_OK) return rc;
+    }
+    rc = launch_attn_window(c, q, k, v, phi, out, debug, B, H, T, HW, d, chunk, overlap, c0,
+                            n_chunks, qtiles, stab_mode, /*bidir=*/false);
     if (rc != REHYAT_OK) return rc;
   }
   return REHYAT_OK;
@@ -323,13 +416,13 @@ int forward_bidirectional(const void* q, const void* k, const void* v, const reh
 
 extern "C" {
 
-int rehyat_version(void) { return 100; }
+int rehyat_version(void) { return 200; }
 
 const char* rehyat_status_string(int code) {
   switch (code) {
     case REHYAT_OK: return "ok";
     case REHYAT_E_NULL: return "a required pointer is NULL";
-    case REHYAT_E_SHAPE: return "a size is non-positive or inconsistent";
+    case REHYAT_E_SHAPE: return "a size is non-positive or inconsistent, or a pointer is misaligned";
     case REHYAT_E_UNSUPPORTED: return "configuration not supported by this build";
     case REHYAT_E_WORKSPACE: return "workspace missing, too small or misaligned";
     case REHYAT_E_HIP: return "a HIP runtime call failed";
@@ -339,9 +432,13 @@ const char* rehyat_status_string(int code) {
 
 const char* rehyat_last_hip_error(void) { return g_hip_err; }
 
+const char* rehyat_attn_kernel_name(int d) { return (d == 64 || d == 128) ? attn_kernel_name(d) : ""; }
+
 int rehyat_chunk_plan(int T, int HW, int chunk, int overlap, int64_t* table, int* n_chunks) {
   if (!n_chunks) return REHYAT_E_NULL;
   if (T < 1 || HW < 1 || chunk < 1 || overlap < 0) return REHYAT_E_SHAPE;
+  if (chunk > T) chunk = T;      // same plan, and no sum below can overflow
+  if (overlap > T) overlap = T;
   const int nc = num_chunks(T, chunk);
   if (table) {
     for (int t = 0; t < nc; ++t) {
@@ -360,7 +457,7 @@ int rehyat_chunk_plan(int T, int HW, int chunk, int overlap, int64_t* table, int
 
 size_t rehyat_workspace_bytes(int B, int H, int d, int dprime) {
   if (B < 1 || H < 1 || !supported_dims(d, dprime)) return 0;
-  return ws_layout(B, H, d, dprime).total;
+  return ws_layout(B, H, d, dprime, kSlots).total;
 }
 
 int rehyat_set_workspace(void* dev_ptr, size_t bytes) {
@@ -395,62 +492,35 @@ int rehyat_shutdown(void) {
 int rehyat_forward_ex(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
                       void* out, int B, int H, int T, int HW, int d, int chunk, int overlap,
                       int causal, int stab_mode, const rehyat_debug_out* debug, void* stream) {
-  if (!q || !k || !v || !out) return REHYAT_E_NULL;
-  if (B < 1 || H < 1 || T < 1 || HW < 1 || d < 1 || chunk < 1 || overlap < 0) return REHYAT_E_SHAPE;
-  if ((int64_t)T * HW >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
-  if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
-  {
-    // one launch covers up to 32 chunks: its workgroup count must fit an int
-    const int64_t cf = chunk < T ? chunk : T;
-    const int64_t tiles = (cf * HW + 63) / 64;
-    if ((int64_t)B * H * kStateSlots * tiles >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
-    // tile offsets inside one softmax window or state segment are 32-bit
-    int64_t wf = (int64_t)chunk + overlap;
-    if (wf > T) wf = T;
-    if (wf * HW * d * 2 >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
-  }
-  if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
-  int rc = check_phi(phi, d);
+  int rc = validate_forward(q, k, v, phi, out, B, H, T, HW, d, &chunk, &overlap, causal, stab_mode);
   if (rc != REHYAT_OK) return rc;
-  if (stab_mode != REHYAT_STAB_ROWMAX && stab_mode != REHYAT_STAB_NONE) return REHYAT_E_SHAPE;
-  if (causal != 0 && causal != 1) return REHYAT_E_SHAPE;
-  const int dp = phi->dprime;
-  hipStream_t st = (hipStream_t)stream;
-
   std::lock_guard<std::mutex> lock(g_mu);
-  const WsLayout L = ws_layout(B, H, d, dp);
-  char* ws = nullptr;
-  rc = ensure_workspace(L.total, &ws);
+  Ctx c;
+  c.sl = kSlots;
+  c.L = ws_layout(B, H, d, phi->dprime, c.sl);
+  c.st = (hipStream_t)stream;
+  c.prof = true;
+  rc = ensure_workspace(c.L.total, c.st, &c.ws);
   if (rc != REHYAT_OK) return rc;
-  if (causal == 0)
-    return forward_bidirectional(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, dp, chunk, overlap,
-                                 stab_mode, st);
+  return forward_core(c, q, k, v, phi, out, debug, B, H, T, HW, d, chunk, overlap, causal, stab_mode);
+}
 
-  const int nc = num_chunks(T, chunk);
-  const int nsplit = choose_nsplit(B * H, nc - 1);
-  int win = kPartialSlots / nsplit;
-  if (win > kStateSlots) win = kStateSlots;
-  const int chunk_frames = chunk < T ? chunk : T;
-  const int qtile = attn_query_tile(d);
-  const int qtiles = (int)(((int64_t)chunk_frames * HW + qtile - 1) / qtile);
-
-  for (int c0 = 0; c0 < nc; c0 += win) {
-    const int c1 = (c0 + win < nc) ? c0 + win : nc;
-    const int n_chunks = c1 - c0;
-    const int n_seg = (c1 < nc) ? n_chunks : n_chunks - 1;
-    if (n_seg > 0) {
-      rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, chunk, overlap, c0, n_seg, nsplit, st);
-      if (rc != REHYAT_OK) return rc;
-    }
-    if (nc > 1) {
-      rc = launch_prefix_window(ws, L, B, H, d, dp, n_chunks, n_seg, nsplit, c0 == 0, st);
-      if (rc != REHYAT_OK) return rc;
-    }
-    rc = launch_attn_window(q, k, v, phi, out, debug, ws, L, B, H, T, HW, d, chunk, overlap, c0,
-                            n_chunks, qtiles, stab_mode, /*bidir=*/false, st);
-    if (rc != REHYAT_OK) return rc;
-  }
-  return REHYAT_OK;
+int rehyat_forward_ws(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                      void* out, int B, int H, int T, int HW, int d, int chunk, int overlap,
+                      int causal, int stab_mode, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  int rc = validate_forward(q, k, v, phi, out, B, H, T, HW, d, &chunk, &overlap, causal, stab_mode);
+  if (rc != REHYAT_OK) return rc;
+  if (!workspace) return REHYAT_E_NULL;
+  Ctx c;
+  c.sl = kSlots;
+  c.L = ws_layout(B, H, d, phi->dprime, c.sl);
+  c.st = (hipStream_t)stream;
+  c.prof = false;
+  if ((((uintptr_t)workspace) & 255) || workspace_bytes < c.L.total) return REHYAT_E_WORKSPACE;
+  c.ws = (char*)workspace;
+  // no library state is touched: calls with distinct workspaces may run concurrently
+  return forward_core(c, q, k, v, phi, out, nullptr, B, H, T, HW, d, chunk, overlap, causal, stab_mode);
 }
 
 int rehyat_profile_enable(int on) {
@@ -501,14 +571,22 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   int rc = check_phi(phi, d);
   if (rc != REHYAT_OK) return rc;
   if (stab_mode != REHYAT_STAB_ROWMAX && stab_mode != REHYAT_STAB_NONE) return REHYAT_E_SHAPE;
+  if (!aligned16(q_t) || !aligned16(k_win) || !aligned16(v_win) || !aligned16(out_t) ||
+      !aligned4(S) || !aligned4(z))
+    return REHYAT_E_SHAPE;
   const int dp = phi->dprime;
   hipStream_t st = (hipStream_t)stream;
 
   std::lock_guard<std::mutex> lock(g_mu);
-  const WsLayout L = ws_layout(B, H, d, dp);
-  char* ws = nullptr;
-  rc = ensure_workspace(L.total, &ws);
+  Ctx c;
+  c.sl = kSlots;
+  c.L = ws_layout(B, H, d, dp, c.sl);
+  c.st = st;
+  c.prof = true;
+  rc = ensure_workspace(c.L.total, st, &c.ws);
   if (rc != REHYAT_OK) return rc;
+  char* ws = c.ws;
+  const WsLayout& L = c.L;
 
   // caller's state -> carry
   StateInArgs in;
@@ -526,7 +604,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   if (n_absorb > 0) {
     // one segment only: enough pieces to cover the chip, none shorter than a tile
     nsplit = (2 * kCUs + B * H - 1) / (B * H);
-    if (nsplit > kPartialSlots) nsplit = kPartialSlots;
+    if (nsplit > c.sl.partial) nsplit = c.sl.partial;
     const int max_pieces = (n_absorb + 63) / 64;
     if (nsplit > max_pieces) nsplit = max_pieces;
     StateArgs s;
@@ -543,18 +621,18 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
     s.chunk0 = 0;
     s.n_seg = 1;
     s.nsplit = nsplit;
-    s.partial_slots = kPartialSlots;
+    s.partial_slots = c.sl.partial;
     s.n_items = B * H * nsplit;
     s.items_per_xcd = (s.n_items + 7) / 8;
     s.kv_bh_stride = (int64_t)n_win * d;
     s.step_n = n_absorb;
-    ProfScope prof(0, st);
+    ProfScope prof(true, 0, st);
     e = launch_state(s, d, s.items_per_xcd * 8, st);
     if (e != hipSuccess) return hip_fail(e, "state kernel launch");
   }
   // slot 0 <- state before the increment (what the read-out uses); carry += increment
-  rc = launch_prefix_window(ws, L, B, H, d, dp, /*n_chunks=*/1, /*n_seg=*/n_absorb > 0 ? 1 : 0, nsplit,
-                            /*first=*/false, st);
+  rc = launch_prefix_window(c, B, H, d, dp, /*n_chunks=*/1, /*n_seg=*/n_absorb > 0 ? 1 : 0, nsplit,
+                            /*first=*/false);
   if (rc != REHYAT_OK) return rc;
 
   AttnArgs a;
@@ -577,7 +655,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   a.n_win_chunks = 1;
   const int qtile = attn_query_tile(d);
   a.qtiles = (n_q + qtile - 1) / qtile;
-  a.state_slots = kStateSlots;
+  a.state_slots = c.sl.state;
   a.stab_mode = stab_mode;
   a.n_items = B * H * a.qtiles;
   a.items_per_xcd = (a.n_items + 7) / 8;
@@ -587,7 +665,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   a.step_nwin = n_win;
   a.all_linear = 0;
   {
-    ProfScope prof(2, st);
+    ProfScope prof(true, 2, st);
     e = launch_attn(a, d, a.items_per_xcd * 8, st);
   }
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
@@ -611,36 +689,39 @@ int rehyat_state(const void* k, const void* v, const rehyat_phi_params* phi, flo
   if (B < 1 || H < 1 || T < 1 || HW < 1 || d < 1) return REHYAT_E_SHAPE;
   if (upto_frames < 0 || upto_frames > T) return REHYAT_E_SHAPE;
   if ((int64_t)T * HW >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  if ((int64_t)B * H > 65535) return REHYAT_E_SHAPE;
   if (d != 64 && d != 128) return REHYAT_E_UNSUPPORTED;
   int rc = check_phi(phi, d);
   if (rc != REHYAT_OK) return rc;
+  if (!aligned16(k) || !aligned16(v) || !aligned4(S_out) || !aligned4(z_out)) return REHYAT_E_SHAPE;
   const int dp = phi->dprime;
   hipStream_t st = (hipStream_t)stream;
-  const size_t BH = (size_t)B * H;
-  if (upto_frames == 0) {
-    hipError_t e = hipMemsetAsync(S_out, 0, BH * d * dp * sizeof(float), st);
-    if (e == hipSuccess) e = hipMemsetAsync(z_out, 0, BH * dp * sizeof(float), st);
-    if (e != hipSuccess) return hip_fail(e, "hipMemsetAsync(state)");
+  if (upto_frames == 0) {  // s_0 = 0, z_0 = 0 (Eq. 14-15): a fill kernel, no workspace
+    hipError_t e = launch_zero_state(S_out, z_out, B * H, d, dp, st);
+    if (e != hipSuccess) return hip_fail(e, "state fill kernel launch");
     return REHYAT_OK;
   }
   std::lock_guard<std::mutex> lock(g_mu);
-  const WsLayout L = ws_layout(B, H, d, dp);
-  char* ws = nullptr;
-  rc = ensure_workspace(L.total, &ws);
+  Ctx c;
+  c.sl = kSlots;
+  c.L = ws_layout(B, H, d, dp, c.sl);
+  c.st = st;
+  c.prof = true;
+  rc = ensure_workspace(c.L.total, st, &c.ws);
   if (rc != REHYAT_OK) return rc;
   // one frame per chunk, no overlap: segment f is frame f
-  const int nsplit = choose_nsplit(B * H, upto_frames);
-  int win = kPartialSlots / nsplit;
-  if (win > kStateSlots) win = kStateSlots;
+  const int nsplit = choose_nsplit(B * H, upto_frames, c.sl);
+  int win = c.sl.partial / nsplit;
+  if (win > c.sl.state) win = c.sl.state;
   for (int c0 = 0; c0 < upto_frames; c0 += win) {
     const int n_seg = (upto_frames - c0 < win) ? upto_frames - c0 : win;
-    rc = launch_state_window(k, v, phi, ws, L, B, H, T, HW, d, 1, 0, c0, n_seg, nsplit, st);
+    rc = launch_state_window(c, k, v, phi, B, H, T, HW, d, 1, 0, c0, n_seg, nsplit);
     if (rc != REHYAT_OK) return rc;
-    rc = launch_prefix_window(ws, L, B, H, d, dp, n_seg, n_seg, nsplit, c0 == 0, st);
+    rc = launch_prefix_window(c, B, H, d, dp, n_seg, n_seg, nsplit, c0 == 0);
     if (rc != REHYAT_OK) return rc;
   }
   StateOutArgs o;
-  o.carry = (const float*)(ws + L.carry);
+  o.carry = (const float*)(c.ws + c.L.carry);
   o.S_out = S_out;
   o.z_out = z_out;
   o.BH = B * H;

@@ -20,6 +20,7 @@
 // All operands that are shared by the four waves (K and V tiles, then W1, W2
 // and the chunk state) travel global -> LDS with direct loads into four LDS
 // tile buffers, issued one or more steps ahead of their use.
+#include <cstdio>
 #include <type_traits>
 #include <utility>
 
@@ -675,6 +676,13 @@ attn_kernel(AttnArgs a) {
 }
 
 int attn_query_tile(int d) { return AttnShape<128, kAttnQB, kAttnNW>::QT; }
+
+const char* attn_kernel_name(int d) {
+  static char name[2][48];
+  char* n = name[d == 128 ? 0 : 1];
+  snprintf(n, sizeof(name[0]), "attn_kernel<%d, %d, %d>", d == 128 ? 128 : 64, kAttnQB, kAttnNW);
+  return n;
+}
 
 hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream) {
   if (d == 128) {

@@ -32,7 +32,8 @@ struct ChunkRange {
 };
 
 __host__ __device__ inline int num_chunks(int T, int chunk) {
-  return (T + chunk - 1) / chunk;
+  // 64-bit: chunk may be as large as INT_MAX ("one chunk covers everything")
+  return (int)(((int64_t)T + chunk - 1) / chunk);
 }
 
 __host__ __device__ inline ChunkRange chunk_range(int T, int HW, int chunk, int overlap, int t) {

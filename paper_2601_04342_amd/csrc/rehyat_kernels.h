@@ -110,8 +110,11 @@ hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream)
 hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream);
 hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream);
 int attn_query_tile(int d);  // query tokens per workgroup of the attention kernel
+const char* attn_kernel_name(int d);  // the instance launched for head width d, as profilers show it
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream);
 hipError_t launch_state_in(const StateInArgs& a, hipStream_t stream);
 hipError_t launch_bidir_state(const BidirArgs& a, hipStream_t stream);
+// S [BH, dprime, d] and z [BH, dprime] <- 0
+hipError_t launch_zero_state(float* S, float* z, int BH, int d, int dprime, hipStream_t stream);
 
 }  // namespace rehyat

@@ -102,6 +102,21 @@ state_in_kernel(StateInArgs a) {
   if (i < a.dprime) c[n + i] = a.z_in[(int64_t)bh * a.dprime + i];
 }
 
+// s_0 = 0, z_0 = 0 (Eq. 14-15) in the layout of the public state hook
+__global__ void __launch_bounds__(256)
+zero_state_kernel(float* S, float* z, int64_t n_s, int64_t n_z) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n_s) S[i] = 0.f;
+  if (i < n_z) z[i] = 0.f;
+}
+
+hipError_t launch_zero_state(float* S, float* z, int BH, int d, int dprime, hipStream_t stream) {
+  const int64_t n_s = (int64_t)BH * d * dprime, n_z = (int64_t)BH * dprime;
+  hipLaunchKernelGGL(zero_state_kernel, dim3((unsigned)((n_s + 255) / 256)), dim3(256), 0, stream, S, z,
+                     n_s, n_z);
+  return hipGetLastError();
+}
+
 hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream) {
   dim3 grid((a.elems / 4 + 255) / 256, a.BH);
   hipLaunchKernelGGL(prefix_kernel, grid, dim3(256), 0, stream, a);

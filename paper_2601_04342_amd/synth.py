@@ -51,6 +51,9 @@ WORKLOADS = {
     "p320_t101_c3": Workload("p320_t101_c3", B=1, H=12, d=128, T=101, HW=20 * 30, chunk=3),
     "p320_t21_c5": Workload("p320_t21_c5", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=5),
     "p320_t21_c7": Workload("p320_t21_c7", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=7),
+    # two chunks; with T_o = 8 the second chunk's window leaves 3 of the 21 frames outside
+    # (bidirectional sets with a small complement)
+    "p320_t21_c11": Workload("p320_t21_c11", B=1, H=12, d=128, T=21, HW=20 * 30, chunk=11),
 }
 
 

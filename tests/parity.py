@@ -20,6 +20,11 @@ NL_REL = 1e-2
 AVG_ABS = 1e-2   # aS/nS and aL/nL are weighted averages of v, scale O(1)
 
 
+def nan_like(t):
+    """An output buffer in which every element a kernel fails to write stays NaN."""
+    return torch.full_like(t, float("nan"))
+
+
 def to_device(q, k, v, phi):
     dq, dk, dv = (x.to("cuda", torch.bfloat16).contiguous() for x in (q, k, v))
     return dq, dk, dv, binding.phi_to_device(phi)
@@ -36,17 +41,26 @@ def oracle_inputs(q, k, v, phi, heads=None, batch=None):
             {n: p.double().numpy() for n, p in phi.items()})
 
 
-def compare(out, comps, ref, stab=0, rows=None, label="", out_scale=1.0):
+def compare(out, comps, ref, stab=0, rows=None, label="", bf16_output_allowance=False):
     """out/comps: GPU results already restricted to the oracle's (b, h) subset,
-    full token axis; ref: oracle Components on `rows` (None = all).  `out_scale`
-    widens the absolute bars on the output for cases whose outputs exceed O(1): the
-    bf16 output alone is off by up to 2^-9 of its magnitude."""
+    full token axis; ref: oracle Components on `rows` (None = all).
+
+    `bf16_output_allowance` is for cases whose outputs exceed O(1) (peaked rows that
+    return nearly one row of v, |y| up to about 4): storing y in bf16 alone moves an
+    element by up to half an ulp = 2^-9 |y| (2^-8 |y| at the bottom of a binade) and by
+    2^-10 |y| to 2^-11 |y| on average, which at |y| >= 2.56 is already more than the absolute bars.
+    The flag adds exactly that storage term, per element, to the bars on the bf16 output;
+    the fp32 components keep their own bars."""
     sel = slice(None) if rows is None else rows
     o = out.float().cpu().double().numpy()[:, :, sel]
     assert np.isfinite(o).all(), label
     err = np.abs(o - ref.out)
-    assert err.max() <= OUT_MAX_ABS * out_scale, (label, "out max-abs", err.max())
-    assert err.mean() <= OUT_MEAN_ABS * out_scale, (label, "out mean-abs", err.mean())
+    if bf16_output_allowance:
+        assert (err <= OUT_MAX_ABS + 2.0 ** -8 * np.abs(ref.out)).all(), (label, "out max-abs", err.max())
+        assert err.mean() <= OUT_MEAN_ABS + 2.0 ** -10 * np.abs(ref.out).mean(), (label, "out mean-abs", err.mean())
+    else:
+        assert err.max() <= OUT_MAX_ABS, (label, "out max-abs", err.max())
+        assert err.mean() <= OUT_MEAN_ABS, (label, "out mean-abs", err.mean())
     if comps is None:
         return err.max(), err.mean()
     c = {n: t.cpu().double().numpy()[:, :, sel] for n, t in comps.items()}
@@ -61,12 +75,12 @@ def compare(out, comps, ref, stab=0, rows=None, label="", out_scale=1.0):
         nL, aL = ref.nL * sc, ref.aL * sc[..., None]
     assert (np.abs(c["nS"] - nS) <= NS_REL * nS).all(), (label, "nS")
     assert (np.abs(c["nL"] - nL) <= NL_REL * nL + 1e-30).all(), (label, "nL")
-    assert np.abs(c["aS"] / c["nS"][..., None] - aS / nS[..., None]).max() <= AVG_ABS * out_scale, (label, "aS")
+    assert np.abs(c["aS"] / c["nS"][..., None] - aS / nS[..., None]).max() <= AVG_ABS, (label, "aS")
     has_l = nL > 0
     if has_l.any():
         g = c["aL"][has_l] / c["nL"][has_l][..., None]
         r = aL[has_l] / nL[has_l][..., None]
-        assert np.abs(g - r).max() <= AVG_ABS * out_scale, (label, "aL")
+        assert np.abs(g - r).max() <= AVG_ABS, (label, "aL")
     assert (c["nL"][~has_l] == 0).all() and (c["aL"][~has_l] == 0).all(), (label, "empty linear set")
     return err.max(), err.mean()
 
@@ -85,7 +99,7 @@ def run_case(B, H, T, HW, d, chunk, overlap=0, stab=0, gain=1.0, rms=True, seed=
         phi = synth.make_phi(H, d, seed=seed + 1, gain=gain)
     dq, dk, dv, dphi = to_device(q, k, v, phi)
     res = binding.forward(dq, dk, dv, dphi, T, HW, chunk, overlap=overlap, stab_mode=stab,
-                          debug=debug, causal=causal)
+                          debug=debug, causal=causal, out=nan_like(dq))
     torch.cuda.synchronize()
     out, comps = res if debug else (res, None)
     ref = cref.forward(*oracle_inputs(q, k, v, phi), T, HW, chunk, overlap=overlap, stab=stab,

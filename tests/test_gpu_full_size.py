@@ -1,7 +1,10 @@
 """GPU parity at the full benchmark shapes, in the launch configuration the
-benchmark times (plain rehyat_forward, library-owned workspace).  The oracle
-evaluates sampled query rows of sampled heads one by one (chunk-recurrent
-form); properties that hold at any size cover the rest."""
+benchmark times (plain rehyat_forward, library-owned workspace).  The headline
+workload is compared in full -- every element of every head, and the five
+components of Eq. 5-9 -- against the oracle; the other full-size workloads on
+sampled query rows of sampled heads (chunk, workgroup and wave edges plus random
+rows).  Every output buffer starts as NaN, so an element that no workgroup
+wrote fails the comparison."""
 import numpy as np
 import pytest
 import torch
@@ -16,9 +19,13 @@ pytestmark = pytest.mark.gpu
 def sample_rows(w, overlap=0, n_random=24, seed=0):
     plan = cref.chunk_plan(w.T, w.HW, w.chunk, overlap)
     rows = set()
+    for t in range(len(plan)):
+        q_lo, q_hi = int(plan[t, 0]), int(plan[t, 1])
+        rows.update([q_lo, q_hi - 1])                            # first and last row of every chunk
     for t in (0, 1, len(plan) // 2, len(plan) - 1):
         q_lo, q_hi = int(plan[t, 0]), int(plan[t, 1])
-        rows.update([q_lo, q_lo + 255, q_lo + 256, q_hi - 1])   # tile and chunk edges
+        # edges of the 32-query waves and 128-query workgroups, and the ragged last workgroup
+        rows.update([q_lo + 31, q_lo + 32, q_lo + 127, q_lo + 128, q_hi - 24, q_hi - 25])
     rng = np.random.default_rng(seed)
     rows.update(int(x) for x in rng.integers(0, w.N, n_random))
     return np.array(sorted(r for r in rows if 0 <= r < w.N), dtype=np.int64)
@@ -29,14 +36,16 @@ def check_workload(name, heads, batches=(0,), overlap=0, debug=False, gain=1.0, 
     print(f"[gpu-test] full size {name} heads {heads} batches {batches} gain {gain}", flush=True)
     q, k, v, phi = synth.make_workload(w, gain=gain)
     dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    out = parity.nan_like(dq)
     if overlap == 0 and not debug and causal:
-        out, comps = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, plain=True), None
+        binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, plain=True, out=out)
+        comps = None
     else:
         res = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, overlap=overlap, debug=debug,
-                              causal=causal)
-        out, comps = res if debug else (res, None)
+                              causal=causal, out=out)
+        comps = res[1] if debug else None
     torch.cuda.synchronize()
-    assert torch.isfinite(out.float()).all()
+    assert torch.isfinite(out.float()).all()   # every element was written
     rows = sample_rows(w, overlap)
     worst = (0.0, 0.0)
     for b in batches:
@@ -51,8 +60,31 @@ def check_workload(name, heads, batches=(0,), overlap=0, debug=False, gain=1.0, 
     return out, worst
 
 
-def test_wan480p_sampled_rows_with_components():
-    check_workload("wan480p", heads=[0, 11], debug=True)
+def test_wan480p_every_element_of_every_head():
+    """The headline workload in full: all 12 x 32,760 x 128 outputs of the call the
+    benchmark times, and the five components m, n^S, a^S, n^L, a^L of every row,
+    against the oracle's evaluation of all heads."""
+    w = synth.WORKLOADS["wan480p"]
+    print("[gpu-test] wan480p, every element, all heads", flush=True)
+    q, k, v, phi = synth.make_workload(w)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    out = parity.nan_like(dq)
+    binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, plain=True, out=out)
+    torch.cuda.synchronize()
+    ref = cref.forward(*parity.oracle_inputs(q, k, v, phi), w.T, w.HW, w.chunk)
+    print("   oracle done", flush=True)
+    e = parity.compare(out, None, ref, label="wan480p all heads")
+    print(f"   all heads: max-abs {e[0]:.2e} mean-abs {e[1]:.2e} "
+          f"linear share {parity.linear_share(ref):.2f}", flush=True)
+    out2 = parity.nan_like(dq)
+    _, comps = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, debug=True, out=out2)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, out)   # the component outputs do not change the result
+    for h in range(w.H):            # head by head to bound the host memory of the comparison
+        rh = cref.Components(*(getattr(ref, n)[:, h:h + 1] for n in ("out", "m", "nS", "aS", "nL", "aL")))
+        ch = {n: t[:, h:h + 1] for n, t in comps.items()}
+        parity.compare(out2[:, h:h + 1], ch, rh, label=f"wan480p components h{h}")
+    print("   components of all heads match", flush=True)
 
 
 def test_wan480p_bench_configuration():
@@ -82,9 +114,12 @@ def test_320x480_shapes(name, overlap):
     check_workload(name, heads=[4, 9], overlap=overlap, debug=(overlap == 1))
 
 
-@pytest.mark.parametrize("name,overlap", [("wan480p", 0), ("wan480p_long", 1), ("p320_t21_c3", 1)])
+@pytest.mark.parametrize("name,overlap", [("wan480p", 0), ("wan480p_long", 1), ("p320_t21_c3", 1),
+                                          ("p320_t21_c7", 2), ("p320_t21_c11", 8)])
 def test_bidirectional_full_size(name, overlap):
-    """Eq. 11-12 at the bench shapes (the paper's causality ablation, Table 6)."""
+    """Eq. 11-12 at the bench shapes (the paper's causality ablation, Table 6), including
+    large windows: T_c = 7, T_o = 2 (9 of 21 frames inside) and T_c = 11, T_o = 8, whose
+    second window leaves only 3 frames to the linear part (state = total - window sums)."""
     check_workload(name, heads=[6], overlap=overlap, debug=True, gain=0.35, causal=False)
 
 
@@ -123,7 +158,7 @@ def test_long_video_flat_workspace():
             torch.cuda.synchronize()
         q, k, v, phi = synth.make_workload(w41)
         dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
-        out = torch.empty_like(dq)
+        out = parity.nan_like(dq)
         torch.cuda.synchronize()
         free_before = torch.cuda.mem_get_info()[0]
         binding.forward(dq, dk, dv, dphi, w41.T, w41.HW, w41.chunk, out=out, plain=True)
@@ -141,8 +176,9 @@ def test_wan720p_and_full_softmax_comparison():
     out, _ = check_workload("wan720p", heads=[4])
     q, k, v, phi = synth.make_workload(w)
     dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
-    full = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.T, plain=True)
+    full = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.T, plain=True, out=parity.nan_like(dq))
     torch.cuda.synchronize()
+    assert torch.isfinite(full.float()).all()
     rows = np.random.default_rng(1).integers(0, w.N, 16)
     h = 4
     qs = q[0, h, rows].double()

@@ -70,7 +70,10 @@ def test_workspace_size_is_independent_of_video_length():
     assert binding.workspace_bytes(1, 12, 128, dprime=128) == 0
 
 
-def _phi(hidden=128, dprime=128, degree=2, act=0, fill=1):
+A = 0x1000   # a non-null, 16-byte aligned fake device pointer (never dereferenced)
+
+
+def _phi(hidden=128, dprime=128, degree=2, act=0, fill=A):
     p = binding.PhiParams()
     for n in ("w1_q", "b1_q", "w2_q", "b2_q", "w1_k", "b1_k", "w2_k", "b2_k"):
         setattr(p, n, fill)
@@ -85,42 +88,42 @@ def test_forward_argument_validation_without_gpu():
     ok = _phi()
     fwd = lambda *a: lib.rehyat_forward(*a)
     P = ctypes.byref
-    assert fwd(None, 1, 1, P(ok), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
-    assert fwd(1, 1, 1, P(ok), None, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
-    assert fwd(1, 1, 1, None, 1, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
-    assert fwd(1, 1, 1, P(_phi(fill=None)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
+    assert fwd(None, A, A, P(ok), A, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
+    assert fwd(A, A, A, P(ok), None, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
+    assert fwd(A, A, A, None, A, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
+    assert fwd(A, A, A, P(_phi(fill=None)), A, 1, 2, 4, 8, 64, 1, None) == binding.E_NULL
     for bad in ((0, 2, 4, 8, 64, 1), (1, 0, 4, 8, 64, 1), (1, 2, 0, 8, 64, 1),
                 (1, 2, 4, 0, 64, 1), (1, 2, 4, 8, 64, 0), (1, 2, 4, 8, 0, 1),
                 (1, 2, 70000, 70000, 64, 1)):
-        assert fwd(1, 1, 1, P(ok), 1, *bad, None) == binding.E_SHAPE, bad
+        assert fwd(A, A, A, P(ok), A, *bad, None) == binding.E_SHAPE, bad
     # one softmax window of 2^31 bytes or more per head; more workgroups than an int counts
-    assert fwd(1, 1, 1, P(ok), 1, 1, 2, 64, 1 << 18, 128, 64, None) == binding.E_SHAPE
-    assert fwd(1, 1, 1, P(ok), 1, 60000, 1, 4, 1 << 22, 128, 1, None) == binding.E_SHAPE
-    assert fwd(1, 1, 1, P(ok), 1, 1, 2, 4, 8, 32, 1, None) == binding.E_UNSUPPORTED
-    assert fwd(1, 1, 1, P(_phi(hidden=64)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
-    assert fwd(1, 1, 1, P(_phi(degree=4)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
-    assert fwd(1, 1, 1, P(_phi(degree=3)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_SHAPE
-    assert fwd(1, 1, 1, P(_phi(act=1)), 1, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
+    assert fwd(A, A, A, P(ok), A, 1, 2, 64, 1 << 18, 128, 64, None) == binding.E_SHAPE
+    assert fwd(A, A, A, P(ok), A, 60000, 1, 4, 1 << 22, 128, 1, None) == binding.E_SHAPE
+    assert fwd(A, A, A, P(ok), A, 1, 2, 4, 8, 32, 1, None) == binding.E_UNSUPPORTED
+    assert fwd(A, A, A, P(_phi(hidden=64)), A, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
+    assert fwd(A, A, A, P(_phi(degree=4)), A, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
+    assert fwd(A, A, A, P(_phi(degree=3)), A, 1, 2, 4, 8, 64, 1, None) == binding.E_SHAPE
+    assert fwd(A, A, A, P(_phi(act=1)), A, 1, 2, 4, 8, 64, 1, None) == binding.E_UNSUPPORTED
     ex = lambda *a: lib.rehyat_forward_ex(*a)
-    base = (1, 1, 1, P(ok), 1, 1, 2, 4, 8, 64, 1)
+    base = (A, A, A, P(ok), A, 1, 2, 4, 8, 64, 1)
     assert ex(*base, -1, 1, 0, None, None) == binding.E_SHAPE       # negative overlap
     assert ex(*base, 0, 2, 0, None, None) == binding.E_SHAPE
     assert ex(*base, 0, 1, 7, None, None) == binding.E_SHAPE        # unknown stabiliser
     st = lambda *a: lib.rehyat_state(*a)
-    assert st(None, 1, P(ok), 1, 1, 1, 2, 4, 8, 64, 2, None) == binding.E_NULL
-    assert st(1, 1, P(ok), 1, 1, 1, 2, 4, 8, 64, 5, None) == binding.E_SHAPE
-    assert st(1, 1, P(ok), 1, 1, 1, 2, 4, 8, 64, -1, None) == binding.E_SHAPE
+    assert st(None, A, P(ok), A, A, 1, 2, 4, 8, 64, 2, None) == binding.E_NULL
+    assert st(A, A, P(ok), A, A, 1, 2, 4, 8, 64, 5, None) == binding.E_SHAPE
+    assert st(A, A, P(ok), A, A, 1, 2, 4, 8, 64, -1, None) == binding.E_SHAPE
     # rehyat_step(q_t, k_win, v_win, phi, S, z, out_t, B, H, d, n_q, n_win, n_absorb, stab, stream)
     sp = lambda *a: lib.rehyat_step(*a)
-    assert sp(1, 1, 1, P(ok), 1, None, 1, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
-    assert sp(1, None, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
-    assert sp(1, 1, 1, None, 1, 1, 1, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
-    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, 17, 0, None) == binding.E_SHAPE   # absorbs more than the window
-    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, -1, 0, None) == binding.E_SHAPE
-    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 0, 16, 8, 0, None) == binding.E_SHAPE
-    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 0, 0, 0, None) == binding.E_SHAPE
-    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 64, 8, 16, 8, 3, None) == binding.E_SHAPE    # unknown stabiliser
-    assert sp(1, 1, 1, P(ok), 1, 1, 1, 1, 2, 96, 8, 16, 8, 0, None) == binding.E_UNSUPPORTED
+    assert sp(A, A, A, P(ok), A, None, A, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
+    assert sp(A, None, A, P(ok), A, A, A, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
+    assert sp(A, A, A, None, A, A, A, 1, 2, 64, 8, 16, 8, 0, None) == binding.E_NULL
+    assert sp(A, A, A, P(ok), A, A, A, 1, 2, 64, 8, 16, 17, 0, None) == binding.E_SHAPE   # absorbs more than the window
+    assert sp(A, A, A, P(ok), A, A, A, 1, 2, 64, 8, 16, -1, 0, None) == binding.E_SHAPE
+    assert sp(A, A, A, P(ok), A, A, A, 1, 2, 64, 0, 16, 8, 0, None) == binding.E_SHAPE
+    assert sp(A, A, A, P(ok), A, A, A, 1, 2, 64, 8, 0, 0, 0, None) == binding.E_SHAPE
+    assert sp(A, A, A, P(ok), A, A, A, 1, 2, 64, 8, 16, 8, 3, None) == binding.E_SHAPE    # unknown stabiliser
+    assert sp(A, A, A, P(ok), A, A, A, 1, 2, 96, 8, 16, 8, 0, None) == binding.E_UNSUPPORTED
 
 
 def test_set_workspace_rejects_misaligned_pointer():
@@ -135,3 +138,57 @@ def test_binding_rejects_wrong_tensor_types():
     q = torch.zeros(1, 2, 8, 64)
     with pytest.raises(TypeError):
         binding.forward(q, q, q, {}, 2, 4, 1)
+
+
+def test_chunk_longer_than_the_video_is_one_chunk():
+    """chunk >= T is one chunk, also at the largest int (no overflow in the chunk count)."""
+    big = 2**31 - 1
+    for chunk, overlap in ((big, 0), (big, big), (22, 5), (21, 0)):
+        got = binding.chunk_plan(21, 1560, chunk, overlap)
+        assert got.tolist() == [[0, 32760, 0, 32760, 0]], (chunk, overlap)
+    # overlap beyond the video clips to the first frame
+    assert binding.chunk_plan(4, 10, 1, big).tolist() == [[0, 10, 0, 10, 0], [10, 20, 0, 20, 0],
+                                                          [20, 30, 0, 30, 0], [30, 40, 0, 40, 0]]
+
+
+def test_misaligned_tensor_pointers_are_rejected():
+    lib = binding.library()
+    ok = _phi()
+    P = ctypes.byref
+    for bad in ((A + 2, A, A, A), (A, A + 8, A, A), (A, A, A + 4, A), (A, A, A, A + 2)):
+        q, k, v, out = bad
+        assert lib.rehyat_forward(q, k, v, P(ok), out, 1, 2, 4, 8, 64, 1, None) == binding.E_SHAPE
+    w = _phi()
+    w.w2_k = A + 8
+    assert lib.rehyat_forward(A, A, A, P(w), A, 1, 2, 4, 8, 64, 1, None) == binding.E_SHAPE
+    b = _phi()
+    b.b1_q = A + 2
+    assert lib.rehyat_forward(A, A, A, P(b), A, 1, 2, 4, 8, 64, 1, None) == binding.E_SHAPE
+
+
+def test_per_call_workspace_validation():
+    lib = binding.library()
+    ok = _phi()
+    P = ctypes.byref
+    need = binding.workspace_bytes(1, 2, 64)
+    args = (A, A, A, P(ok), A, 1, 2, 4, 8, 64, 1, 0, 1, 0)
+    assert lib.rehyat_forward_ws(*args, None, need, None) == binding.E_NULL
+    assert lib.rehyat_forward_ws(*args, A + 16, need, None) == binding.E_WORKSPACE     # misaligned
+    assert lib.rehyat_forward_ws(*args, A, need - 1, None) == binding.E_WORKSPACE      # too small
+    assert lib.rehyat_forward_ws(None, A, A, P(ok), A, 1, 2, 4, 8, 64, 1, 0, 1, 0, A, need,
+                                 None) == binding.E_NULL
+
+
+def test_caller_owned_workspace_is_never_replaced():
+    """A caller-set workspace that is too small makes the call fail; the library does
+    not allocate one of its own behind the caller's back."""
+    lib = binding.library()
+    ok = _phi()
+    try:
+        assert lib.rehyat_set_workspace(A, 4096) == binding.OK
+        rc = lib.rehyat_forward(A, A, A, ctypes.byref(ok), A, 1, 2, 4, 8, 64, 1, None)
+        assert rc == binding.E_WORKSPACE
+        rc = lib.rehyat_state(A, A, ctypes.byref(ok), A, A, 1, 2, 4, 8, 64, 2, None)
+        assert rc == binding.E_WORKSPACE
+    finally:
+        assert lib.rehyat_set_workspace(None, 0) == binding.OK
