@@ -175,6 +175,31 @@ int rehyat_forward_ws(const void *q, const void *k, const void *v,
                       size_t workspace_bytes, void *stream);
 
 /*
+ * rehyat_forward for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same arguments, same kernels, same result as rehyat_forward, but chunk-state
+ * partial sums, chunk states and the carry live in a fixed array of
+ * REHYAT_NOALLOC_SCRATCH_BYTES (64 MiB) that is part of the library's device
+ * image -- each GPU the library runs on holds it until the process ends --
+ * and the call performs no hipMalloc / hipFree and no allocating library
+ * routine.  The first call on each device looks the array's address up (the
+ * HIP runtime loads that part of the device image then): make that one call
+ * eagerly, outside any capture.  The chunks are processed in windows of as many chunk states
+ * as fit the array (27 per window at B*H = 12, d = 128; at least one), so larger
+ * B*H costs more, shorter launches; when not even one state per (b, h) fits
+ * (B*H above 202 at d = 128) the call returns REHYAT_E_WORKSPACE and launches
+ * nothing.  Nothing has to be cleared between calls: every element a kernel
+ * reads is written earlier in the same call.  All calls on one GPU share that
+ * GPU's array: calls that overlap in time on one GPU race (order them on one
+ * stream); the internal lock only serialises the host side.
+ */
+#define REHYAT_NOALLOC_SCRATCH_BYTES ((size_t)64 << 20)
+int rehyat_forward_noalloc(const void *q, const void *k, const void *v,
+                           const rehyat_phi_params *phi_params, void *out,
+                           int B, int H, int T, int HW, int d, int chunk,
+                           void *stream);
+
+/*
  * One step of the chunk-wise RNN (section 3.3, Eq. 14-18) for generation chunk by
  * chunk: the caller owns the state and the K/V window, the library holds nothing
  * between calls, and peak memory does not depend on how many chunks came before.

@@ -19,7 +19,7 @@ STAB_ROWMAX, STAB_NONE = 0, 1
 
 # every symbol include/rehyat.h declares
 EXPORTS = ("rehyat_chunk_plan", "rehyat_workspace_bytes", "rehyat_set_workspace",
-           "rehyat_forward", "rehyat_forward_ex", "rehyat_forward_ws",
+           "rehyat_forward", "rehyat_forward_ex", "rehyat_forward_ws", "rehyat_forward_noalloc",
            "rehyat_step", "rehyat_state", "rehyat_shutdown",
            "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error",
            "rehyat_attn_kernel_name",
@@ -77,6 +77,9 @@ def _load():
     lib.rehyat_forward_ws.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp,
                                       ci, ci, ci, ci, ci, ci, ci, ci, ci,
                                       vp, ctypes.c_size_t, vp]
+    lib.rehyat_forward_noalloc.restype = ci
+    lib.rehyat_forward_noalloc.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp,
+                                           ci, ci, ci, ci, ci, ci, vp]
     lib.rehyat_step.restype = ci
     lib.rehyat_step.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp, vp, vp,
                                 ci, ci, ci, ci, ci, ci, ci, vp]
@@ -214,14 +217,15 @@ def _check_qkv(q, k, v):
 
 
 def forward(q, k, v, phi, T, HW, chunk, out=None, overlap=0, causal=True,
-            stab_mode=STAB_ROWMAX, debug=False, stream=None, plain=False, workspace=None):
+            stab_mode=STAB_ROWMAX, debug=False, stream=None, plain=False, workspace=None,
+            noalloc=False):
     """Hybrid attention forward.  q, k, v: CUDA bf16 [B, H, T*HW, d].
 
     Returns ``out`` (bf16, same shape), or ``(out, components)`` with
     ``debug=True`` where components is a dict of fp32 tensors m, nS, aS, nL, aL.
     ``plain=True`` calls ``rehyat_forward`` (no extra knobs) instead of
     ``rehyat_forward_ex``; ``workspace`` (a CUDA byte tensor) calls
-    ``rehyat_forward_ws``.
+    ``rehyat_forward_ws``; ``noalloc=True`` calls ``rehyat_forward_noalloc``.
     """
     lib = _load()
     _check_qkv(q, k, v)
@@ -235,11 +239,13 @@ def forward(q, k, v, phi, T, HW, chunk, out=None, overlap=0, causal=True,
         out = torch.empty_like(q)
     s = torch.cuda.current_stream() if stream is None else stream
     sp = ctypes.c_void_p(s.cuda_stream)
-    if plain:
-        rc = lib.rehyat_forward(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(p),
-                                out.data_ptr(), B, H, T, HW, d, chunk, sp)
+    if plain or noalloc:
+        fn, name = ((lib.rehyat_forward_noalloc, "rehyat_forward_noalloc") if noalloc
+                    else (lib.rehyat_forward, "rehyat_forward"))
+        rc = fn(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(p),
+                out.data_ptr(), B, H, T, HW, d, chunk, sp)
         if rc != OK:
-            raise RehyatError(rc, "rehyat_forward")
+            raise RehyatError(rc, name)
         return out
     if workspace is not None:
         rc = lib.rehyat_forward_ws(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(p),

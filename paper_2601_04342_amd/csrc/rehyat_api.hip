@@ -25,6 +25,14 @@ constexpr Slots kSlots{64, 32};  // workspaces sized by rehyat_workspace_bytes
 constexpr int kMaxSplit = 8;
 constexpr int kCUs = 256;
 
+// Device memory of the allocation-free entry point: one array per GPU, alive until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress; the
+// address it returns (per device) is what kernels and the host layer use.
+constexpr size_t kScratchBytes = REHYAT_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+
 struct Workspace {
   void* ptr = nullptr;
   size_t bytes = 0;
@@ -412,6 +420,18 @@ int forward_core(const Ctx& c, const void* q, const void* k, const void* v,
   return REHYAT_OK;
 }
 
+// Largest slot counts whose layout fits `bytes` (equal partial and state slots, at most the
+// default window); 0 slots when not even one fits.
+Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
+  Slots best{0, 0};
+  for (int n = 1; n <= kSlots.state; ++n) {
+    const Slots s{n, n};
+    if (ws_layout(B, H, d, dp, s).total > bytes) break;
+    best = s;
+  }
+  return best;
+}
+
 }  // namespace
 
 extern "C" {
@@ -521,6 +541,38 @@ int rehyat_forward_ws(const void* q, const void* k, const void* v, const rehyat_
   c.ws = (char*)workspace;
   // no library state is touched: calls with distinct workspaces may run concurrently
   return forward_core(c, q, k, v, phi, out, nullptr, B, H, T, HW, d, chunk, overlap, causal, stab_mode);
+}
+
+int rehyat_forward_noalloc(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                           void* out, int B, int H, int T, int HW, int d, int chunk, void* stream) {
+  int overlap = 0;
+  int rc = validate_forward(q, k, v, phi, out, B, H, T, HW, d, &chunk, &overlap, 1, REHYAT_STAB_ROWMAX);
+  if (rc != REHYAT_OK) return rc;
+  Ctx c;
+  c.sl = slots_that_fit(B, H, d, phi->dprime, kScratchBytes);
+  if (c.sl.state < 1) return REHYAT_E_WORKSPACE;  // B*H beyond what the fixed scratch array holds
+  c.L = ws_layout(B, H, d, phi->dprime, c.sl);
+  c.st = (hipStream_t)stream;
+  c.prof = false;
+  std::lock_guard<std::mutex> lock(g_mu);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return REHYAT_E_UNSUPPORTED;
+  if (!g_scratch_ptr[dev]) {
+    // each GPU holds its own copy of the array at its own address
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p || (((uintptr_t)p) & 255)) return REHYAT_E_WORKSPACE;
+    g_scratch_ptr[dev] = p;
+  }
+  c.ws = (char*)g_scratch_ptr[dev];
+  // every element of the scratch that a kernel reads is written earlier in the same call
+  // (partials by the state kernel, states and carry by the prefix pass), so the previous
+  // call's contents need no clearing
+  return forward_core(c, q, k, v, phi, out, nullptr, B, H, T, HW, d, chunk, overlap, 1,
+                      REHYAT_STAB_ROWMAX);
 }
 
 int rehyat_profile_enable(int on) {

@@ -192,3 +192,13 @@ def test_caller_owned_workspace_is_never_replaced():
         assert rc == binding.E_WORKSPACE
     finally:
         assert lib.rehyat_set_workspace(None, 0) == binding.OK
+
+
+def test_noalloc_entry_point_limits():
+    lib = binding.library()
+    big = _phi(hidden=256, dprime=256)
+    P = ctypes.byref
+    # more (batch, head) pairs than the fixed scratch array can hold one chunk state for
+    assert lib.rehyat_forward_noalloc(A, A, A, P(big), A, 17, 12, 4, 8, 128, 1, None) == binding.E_WORKSPACE
+    assert lib.rehyat_forward_noalloc(None, A, A, P(big), A, 1, 12, 4, 8, 128, 1, None) == binding.E_NULL
+    assert lib.rehyat_forward_noalloc(A, A, A, P(big), A, 1, 12, 4, 8, 128, 0, None) == binding.E_SHAPE
