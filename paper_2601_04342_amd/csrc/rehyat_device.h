@@ -172,6 +172,53 @@ __device__ __forceinline__ void tile_load_buffer(__amdgpu_buffer_rsrc_t rsrc, in
   }
 }
 
+// The same direct load written as inline asm, for kernels that rotate tile buffers at run
+// time.  The compiler orders every LDS read after any direct load it can see that might
+// write the same object, by waiting for ALL outstanding loads -- right for one buffer,
+// but with buffers picked by a run-time index it cannot tell the tile being read from the
+// tile being prefetched, and the wait would undo the prefetch.  Loads issued here are
+// invisible to that analysis; callers order them against the reads themselves with
+// wait_loads_and_barrier.  `rsrc` is the descriptor as four scalar words, `soff` a
+// wave-uniform byte offset, `lds_addr` the wave-uniform LDS byte address of the 1 KB block
+// (lane i writes bytes [16 i, 16 i + 16) of it).
+__device__ __forceinline__ u32x4 make_rsrc_words(const void* base) {
+  const uint64_t b = (uint64_t)base;
+  u32x4 w;
+  w[0] = __builtin_amdgcn_readfirstlane((uint32_t)b);
+  w[1] = __builtin_amdgcn_readfirstlane((uint32_t)(b >> 32) & 0xffffu);
+  w[2] = 0x7fffffffu;   // open ended, as in make_rsrc
+  w[3] = 0x00020000u;
+  return w;
+}
+__device__ __forceinline__ void direct_load_16(u32x4 rsrc, int voff, int soff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void* p) {
+  return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
+}
+
+// One tile through direct_load_16.  Rows at or beyond `valid` re-read the last valid row
+// (finite values; callers mask what they compute from them).  Wave w of NW moves the 1 KB
+// blocks w, w+NW, ...; `soff` is the tile's byte offset from the descriptor's base.
+template <int ROWBYTES, int TILE_BYTES, int NW>
+__device__ __forceinline__ void tile_load_asm(u32x4 rsrc, int soff, uint32_t lds_tile, int wave, int lane,
+                                              int valid) {
+  constexpr int CPR = ROWBYTES / 16;     // chunks per row
+  constexpr int RPB = 1024 / ROWBYTES;   // rows per 1 KB block
+  constexpr int NBLK = TILE_BYTES / 1024;
+  static_assert(NBLK % NW == 0, "blocks of a tile are dealt evenly to the waves");
+#pragma unroll
+  for (int n = 0; n < NBLK / NW; ++n) {
+    const int blk = wave + NW * n;
+    int R = blk * RPB + lane / CPR;
+    const int c = (lane % CPR) ^ swz<ROWBYTES>(R);
+    if (R >= valid) R = valid - 1;
+    direct_load_16(rsrc, R * ROWBYTES + c * 16, soff, lds_tile + blk * 1024);
+  }
+}
+
 // Wait until at most N of this wave's direct loads are outstanding (and all of
 // its LDS accesses are done), then workgroup barrier.  Written as one asm block:
 // the compiler's own barrier would wait for every outstanding direct load and

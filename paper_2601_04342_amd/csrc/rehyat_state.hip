@@ -13,10 +13,17 @@
 // it lies in the upper half, and accumulates V^T phi into its d x 32 slice of
 // the state, held in MFMA accumulators for the whole token range.
 //
-// K and V tiles arrive by direct global->LDS loads (chunk-swizzled rows, see
-// tile_load_direct), each issued half a tile step ahead of its first use: the
-// K tile of step t+1 once every wave is past the first half of step t, the V
-// tile of step t+1 once step t is complete.
+// K and V tiles arrive by direct global->LDS loads (chunk-swizzled rows) into two
+// buffers each, picked by the parity of the tile, and are requested two tile
+// steps ahead of their use: K and V are read exactly once, so every tile comes
+// from HBM, whose latency is far longer than the half tile step a single buffer
+// allows.  The K tile of step t+2 is requested once every wave is past the first
+// half of step t (its buffer is free then), the V tile of step t+2 once step t
+// is complete.  The loads are issued through tile_load_asm (see there: with
+// buffers picked at run time the compiler must not see them) and ordered
+// against the reads by counted waits.  With W1 and U the four tile buffers fill
+// the 160 KB of LDS exactly; the first-layer bias is therefore read through
+// scalar loads (it is wave-uniform up to the lane half).
 #include <type_traits>
 
 #include "rehyat_device.h"
@@ -37,10 +44,8 @@ state_kernel(StateArgs a) {
   static_assert(DP / NW == 32, "each wave owns 32 features");
 
   __shared__ __attribute__((aligned(1024))) char W1s[(HID / 64) * TB];
-  __shared__ __attribute__((aligned(1024))) char Xs[TB];
-  __shared__ __attribute__((aligned(1024))) char Vs[TB];
+  __shared__ __attribute__((aligned(1024))) char XV[4 * TB];   // K tiles 0/1, then V tiles 0/1
   __shared__ __attribute__((aligned(1024))) char Us[64 * UROW];
-  __shared__ __attribute__((aligned(16))) float sb1[HID];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -78,7 +83,19 @@ state_kernel(StateArgs a) {
   const bf16_t* W2 = a.w2_k + (int64_t)h * DP * HID;
 
   // ---- resident operands ----------------------------------------------------
-  for (int i = tid; i < HID; i += NT) sb1[i] = a.b1_k[(int64_t)h * HID + i];
+  // first-layer bias of accumulator register 4i+j: hidden unit 32w + 8i + 4g + j -- two
+  // wave-uniform values per register, picked by the lane half
+  float b1lo[16], b1hi[16];
+  {
+    const float* bp = a.b1_k + (int64_t)h * HID + wave * 32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        b1lo[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + j])));
+        b1hi[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + 4 + j])));
+      }
+  }
   const int unit = wave * 32 + r;  // this lane's feature (a column of the wave's products)
   const float b2v = a.b2_k[(int64_t)h * DP + unit];
   // W2 rows of this wave's features as B operands: column = feature, k = hidden
@@ -88,26 +105,30 @@ state_kernel(StateArgs a) {
 #pragma unroll
     for (int ks = 0; ks < KS2; ++ks) w2f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
   }
-  auto contiguous = [](int R) { return R * (2 * D); };
-  // tile `it` of K or V, rows at or beyond `valid` re-read the last valid row
-  const __amdgpu_buffer_rsrc_t Kr = make_rsrc(Kb), Vr = make_rsrc(Vb);
-  auto issue_tile = [&](__amdgpu_buffer_rsrc_t rsrc, const char* gb, char* dst, int it, int valid) {
-    if (valid >= 64) {
-      tile_load_buffer<2 * D, TB, NW>(rsrc, it * TB, dst, wave, lane, contiguous);
-    } else {
-      const char* src = gb + (int64_t)it * TB;
-      auto clamped = [valid](int R) { return (R < valid ? R : valid - 1) * (2 * D); };
-      tile_load_direct<2 * D, TB, NW>(src, dst, wave, lane, clamped);
-    }
-  };
+  // tile `it` of K or V into the buffer of its parity; rows at or beyond the end of the range
+  // re-read the last valid row
+  const u32x4 Kr = make_rsrc_words(Kb), Vr = make_rsrc_words(Vb), W1r = make_rsrc_words(W1);
+  const uint32_t xv_lds = lds_address(XV);
   const int n_tiles = n_full + (rem > 0 ? 1 : 0);
-  auto valid_of = [&](int it) { return it < n_full ? 64 : rem; };
+  constexpr int LPT = TB / (1024 * NW);   // load instructions per wave per tile
+  auto issue_k = [&](int it) {
+    tile_load_asm<2 * D, TB, NW>(Kr, __builtin_amdgcn_readfirstlane(it * TB), xv_lds + (it & 1) * TB, wave, lane,
+                                 it < n_full ? 64 : rem);
+  };
+  auto issue_v = [&](int it) {
+    tile_load_asm<2 * D, TB, NW>(Vr, __builtin_amdgcn_readfirstlane(it * TB), xv_lds + (2 + (it & 1)) * TB, wave,
+                                 lane, it < n_full ? 64 : rem);
+  };
 #pragma unroll
   for (int j = 0; j < HID / 64; ++j)
-    tile_load_buffer<2 * D, TB, NW>(make_rsrc(W1), j * TB, W1s + j * TB, wave, lane, contiguous);
+    tile_load_asm<2 * D, TB, NW>(W1r, j * TB, lds_address(W1s) + j * TB, wave, lane, 64);
   if (n_tiles > 0) {
-    issue_tile(Kr, Kb, Xs, 0, valid_of(0));
-    issue_tile(Vr, Vb, Vs, 0, valid_of(0));
+    issue_k(0);
+    issue_v(0);
+  }
+  if (n_tiles > 1) {
+    issue_k(1);
+    issue_v(1);
   }
 
   // ---- per-lane LDS byte offsets ----------------------------------------------
@@ -143,20 +164,22 @@ state_kernel(StateArgs a) {
   const bool squared = (wave * 32 >= DP / 2);
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  wait_loads_and_barrier<0>();   // W1, first K and V tiles, bias vector
+  // W1 and the first K and V tiles (the second pair may still be in flight).  A wave's loads
+  // complete in the order issued, so "at most the n newest outstanding" means that every
+  // older one has landed.
+  if (n_tiles > 1) wait_loads_and_barrier<2 * LPT>();
+  else wait_loads_and_barrier<0>();
 
   auto tile_step = [&](auto TAILC, int it) {
     constexpr bool TAIL = decltype(TAILC)::value;
+    const char* const Xs = XV + (it & 1) * TB;
+    const char* const Vs = XV + (2 + (it & 1)) * TB;
     // ---- first half: U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden]
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
       f32x16 u;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        f32x4 bias = *reinterpret_cast<const f32x4*>(sb1 + wave * 32 + 8 * i + 4 * g);
-#pragma unroll
-        for (int j = 0; j < 4; ++j) u[4 * i + j] = bias[j];
-      }
+      for (int e = 0; e < 16; ++e) u[e] = g ? b1hi[e] : b1lo[e];
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         bf16x8 wf = *reinterpret_cast<const bf16x8*>(W1s + w1off[ks]);
@@ -172,8 +195,11 @@ state_kernel(StateArgs a) {
         *reinterpret_cast<u32x2*>(Us + uwoff[i] + tb * (32 * UROW)) = pk;
       }
     }
-    wait_loads_and_barrier<0>();   // U complete; this tile's V has landed; X is free
-    if (it + 1 < n_tiles) issue_tile(Kr, Kb, Xs, it + 1, valid_of(it + 1));
+    // U complete; this tile's V has landed (newer: K and V of the next tile); this tile's K
+    // buffer is free
+    if (it + 1 < n_tiles) wait_loads_and_barrier<2 * LPT>();
+    else wait_loads_and_barrier<0>();
+    if (it + 2 < n_tiles) issue_k(it + 2);
     // ---- second half ---------------------------------------------------------------
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
@@ -210,8 +236,12 @@ state_kernel(StateArgs a) {
         }
       }
     }
-    wait_loads_and_barrier<0>();   // next K tile has landed; U and V are free
-    if (it + 1 < n_tiles) issue_tile(Vr, Vb, Vs, it + 1, valid_of(it + 1));
+    // the next K tile has landed (newer: V of the next tile, K of the one after); U and this
+    // tile's V buffer are free
+    if (it + 2 < n_tiles) wait_loads_and_barrier<2 * LPT>();
+    else if (it + 1 < n_tiles) wait_loads_and_barrier<LPT>();
+    else wait_loads_and_barrier<0>();
+    if (it + 2 < n_tiles) issue_v(it + 2);
   };
 
   for (int it = 0; it < n_full; ++it) tile_step(std::false_type{}, it);
