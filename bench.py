@@ -170,12 +170,20 @@ def main():
     if args.mode == "stream":
         out = torch.cat([p[3] for p in pieces], dim=2)
     assert torch.isfinite(out.float()).all()
+    copy_gbps = None
     if args.pmc_copy_mib > 0:
         src = torch.full((args.pmc_copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
+        dst.copy_(src)   # warm-up (also the copy a --pmc run calibrates on: the first of the three)
         torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
         dst.copy_(src)
+        dst.copy_(src)
+        c1.record()
         torch.cuda.synchronize()
+        # bytes read + bytes written per second: what an HBM-bound pass can reach on this machine
+        copy_gbps = 2 * 2 * src.numel() / (c0.elapsed_time(c1) * 1e-3) / 1e9
         del src, dst
 
     fl = algorithmic_flops(w, chunk, overlap, causal)
@@ -209,6 +217,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": binding.attn_kernel_name(w.d), "achieved": achieved,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
+        "copy_GBps": copy_gbps,
         "state_kernel_tflops": (fl["state_kernel"] / (prof["state"][0] / args.steps * 1e-3) / 1e12
                                 if prof["state"][1] else None),
     }

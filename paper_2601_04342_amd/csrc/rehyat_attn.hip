@@ -611,7 +611,10 @@ attn_kernel(AttnArgs a) {
           for (int e = 0; e < 16; ++e) {
             float x = fmaxf(acc[qb][e], 0.f);
             if (squared) x = x * x;
-            x = bf16_round(x * lin_scale[qb]);
+            // the read-out below rounds x to bf16 (MFMA operand); the normaliser takes it
+            // unrounded: the 256 rounding errors of a row have random signs and relative size
+            // 2^-9, far below the bar on n^L, and the rounding costs two instructions per feature
+            x = x * lin_scale[qb];
             acc[qb][e] = x;
             part += x * zv[e];
           }
