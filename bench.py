@@ -29,7 +29,10 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # the same counters in the same runs: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0), keyed by workload
 # and valid for the library version they were measured on (profiles/*_hbm_traffic_pmc.md).
 # Anything else reports null.
-ATTN_TRAFFIC = {}
+ATTN_TRAFFIC = {
+    # 2.0 x 167,900 KiB + 1.0 x 98,280 KiB (profiles/wan480p_hbm_traffic_pmc.md)
+    ("wan480p", "forward", 210): 444_500_000,
+}
 
 
 def algorithmic_flops(w, chunk, overlap=0, causal=True):

@@ -436,7 +436,7 @@ Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
 
 extern "C" {
 
-int rehyat_version(void) { return 200; }
+int rehyat_version(void) { return 210; }
 
 const char* rehyat_status_string(int code) {
   switch (code) {
