@@ -1,0 +1,118 @@
+"""Pins of the gradient oracle (oracle/grad.py: dL/dphi for the distillation step of
+section 3.4, Eq. 19) against things other than itself: central finite differences
+of the independent C forward oracle, the L1 loss of Eq. 19 itself, and cases
+whose gradient is known in closed form.  No GPU."""
+import numpy as np
+import pytest
+
+from oracle import brute, cref, grad
+
+NAMES = ("w1_q", "b1_q", "w2_q", "b2_q", "w1_k", "b1_k", "w2_k", "b2_k")
+
+
+def make(B, H, T, HW, d, hidden, dprime, seed, scale=0.6):
+    rng = np.random.default_rng(seed)
+    N = T * HW
+    q, k, v = (rng.standard_normal((B, H, N, d)) for _ in range(3))
+    shapes = {"w1": (H, hidden, d), "b1": (H, hidden), "w2": (H, dprime, hidden), "b2": (H, dprime)}
+    phi = {n: rng.standard_normal(shapes[n[:2]]) * scale for n in NAMES}
+    G = rng.standard_normal((B, H, N, d))
+    return q, k, v, phi, G
+
+
+def loss_forward(q, k, v, phi, G, T, HW, chunk, overlap):
+    """sum(G * y_hat) with y_hat from the C oracle of the forward pass."""
+    return float((cref.forward(q, k, v, phi, T, HW, chunk, overlap=overlap).out * G).sum())
+
+
+def fd_entries(rng, arr, n):
+    idx = [tuple(rng.integers(0, s) for s in arr.shape) for _ in range(n)]
+    return list(dict.fromkeys(idx))
+
+
+@pytest.mark.parametrize("T,HW,chunk,overlap", [(4, 5, 1, 0), (5, 4, 2, 0), (5, 4, 2, 1), (6, 3, 1, 2)])
+def test_gradients_match_central_differences_of_the_forward_oracle(T, HW, chunk, overlap):
+    B, H, d, hidden, dprime = 2, 2, 6, 10, 8
+    q, k, v, phi, G = make(B, H, T, HW, d, hidden, dprime, seed=T * 100 + chunk * 10 + overlap)
+    grads, y = grad.phi_backward(q, k, v, phi, G, T, HW, chunk, overlap)
+    ref = cref.forward(q, k, v, phi, T, HW, chunk, overlap=overlap).out
+    assert np.abs(y - ref).max() <= 1e-11 * max(1.0, np.abs(ref).max())   # same forward
+    rng = np.random.default_rng(7)
+    eps = 1e-6
+    checked = 0
+    for name in NAMES:
+        scale = max(np.abs(grads[name]).max(), 1e-12)
+        for idx in fd_entries(rng, phi[name], 7):
+            p_hi = {n: a.copy() for n, a in phi.items()}
+            p_lo = {n: a.copy() for n, a in phi.items()}
+            p_hi[name][idx] += eps
+            p_lo[name][idx] -= eps
+            fd = (loss_forward(q, k, v, p_hi, G, T, HW, chunk, overlap)
+                  - loss_forward(q, k, v, p_lo, G, T, HW, chunk, overlap)) / (2 * eps)
+            assert abs(fd - grads[name][idx]) <= 2e-6 * scale + 1e-9, (name, idx, fd, grads[name][idx])
+            checked += 1
+    assert checked >= 40
+
+
+def test_l1_distillation_loss_of_eq_19():
+    """Eq. 19: L = mean |y - y_hat| over the block output; its gradient is the gradient for
+    G = sign(y_hat - y) / count.  Checked by differencing the L1 loss itself, evaluated with
+    the brute-force definition of the forward pass."""
+    B, H, T, HW, d, hidden, dprime, chunk = 1, 2, 4, 4, 6, 8, 6, 1
+    q, k, v, phi, _ = make(B, H, T, HW, d, hidden, dprime, seed=3)
+    teacher = np.random.default_rng(4).standard_normal(q.shape)   # stands in for the softmax teacher's output
+    y = brute.forward(q, k, v, phi, T, HW, chunk)["out"]
+    G = np.sign(y - teacher) / y.size
+    grads, _ = grad.phi_backward(q, k, v, phi, G, T, HW, chunk)
+
+    def l1(p):
+        return float(np.abs(teacher - brute.forward(q, k, v, p, T, HW, chunk)["out"]).mean())
+
+    rng = np.random.default_rng(5)
+    eps = 1e-7   # small enough that no |.| or ReLU kink is crossed for these entries
+    for name in NAMES:
+        scale = max(np.abs(grads[name]).max(), 1e-12)
+        for idx in fd_entries(rng, phi[name], 4):
+            p_hi = {n: a.copy() for n, a in phi.items()}
+            p_lo = {n: a.copy() for n, a in phi.items()}
+            p_hi[name][idx] += eps
+            p_lo[name][idx] -= eps
+            fd = (l1(p_hi) - l1(p_lo)) / (2 * eps)
+            assert abs(fd - grads[name][idx]) <= 1e-5 * scale + 1e-10, (name, idx)
+
+
+def test_one_chunk_has_no_linear_part_hence_zero_gradient():
+    """chunk >= T: every output is plain softmax attention (Eq. 2), independent of phi."""
+    q, k, v, phi, G = make(1, 2, 3, 5, 6, 8, 6, seed=11)
+    grads, _ = grad.phi_backward(q, k, v, phi, G, 3, 5, 3)
+    for name in NAMES:
+        assert np.abs(grads[name]).max() == 0.0
+
+
+def test_gradient_is_linear_in_the_upstream_gradient():
+    q, k, v, phi, G1 = make(1, 2, 4, 4, 6, 8, 6, seed=12)
+    G2 = np.random.default_rng(13).standard_normal(G1.shape)
+    g1, _ = grad.phi_backward(q, k, v, phi, G1, 4, 4, 1)
+    g2, _ = grad.phi_backward(q, k, v, phi, G2, 4, 4, 1)
+    g3, _ = grad.phi_backward(q, k, v, phi, 2.0 * G1 - 0.5 * G2, 4, 4, 1)
+    for name in NAMES:
+        want = 2.0 * g1[name] - 0.5 * g2[name]
+        assert np.abs(g3[name] - want).max() <= 1e-11 * max(1.0, np.abs(want).max())
+
+
+def test_dead_feature_and_first_chunk_queries_get_no_gradient():
+    """A feature whose pre-activation is negative for every token has zero gradient in its
+    row of w2 and its bias; queries of chunk 0 have an empty linear set, so with a single
+    linear-set chunk the query map only sees chunk-1 queries."""
+    q, k, v, phi, G = make(1, 1, 2, 6, 6, 8, 6, seed=14)
+    phi["b2_k"][0, 2] = -1e6
+    phi["b2_q"][0, 4] = -1e6
+    grads, _ = grad.phi_backward(q, k, v, phi, G, 2, 6, 1)
+    assert np.abs(grads["w2_k"][0, 2]).max() == 0.0 and grads["b2_k"][0, 2] == 0.0
+    assert np.abs(grads["w2_q"][0, 4]).max() == 0.0 and grads["b2_q"][0, 4] == 0.0
+    # zeroing the upstream gradient on chunk 1 leaves nothing that depends on phi
+    G0 = G.copy()
+    G0[:, :, 6:] = 0.0
+    g0, _ = grad.phi_backward(q, k, v, phi, G0, 2, 6, 1)
+    for name in NAMES:
+        assert np.abs(g0[name]).max() == 0.0
