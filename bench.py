@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # Anything else reports null.
 ATTN_TRAFFIC = {
     # 2.0 x 167,900 KiB + 1.0 x 98,280 KiB (profiles/wan480p_hbm_traffic_pmc.md)
-    ("wan480p", "forward", 210): 444_500_000,
+    ("wan480p", "forward", 300): 444_500_000,
 }
 
 
@@ -56,6 +56,21 @@ def algorithmic_flops(w, chunk, overlap=0, causal=True):
     return dict(softmax=softmax, phi_q=phi_q, phi_k=phi_k, state=state, readout=readout,
                 total=softmax + phi_q + phi_k + state + readout,
                 attn_kernel=softmax + phi_q + readout, state_kernel=phi_k + state)
+
+
+def backward_flops(w, chunk, fwd):
+    """Algorithmic work of the feature-map gradient (Eq. 19) on top of the forward pass:
+    per query with a linear set and per key in some linear set, dPhi (one read-out-sized
+    product), the chunk-state gradient on the query side, and the two layers' input and
+    weight gradients; phi itself is counted once (in the forward pass)."""
+    from paper_2601_04342_amd import binding
+    plan = binding.chunk_plan(w.T, w.HW, chunk, 0).tolist()
+    BH, d, h, Dp = w.B * w.H, w.d, 2 * w.d, 2 * w.d
+    n_q = sum(r[1] - r[0] for r in plan if r[4] > 0)
+    n_k = plan[-1][4]
+    per_tok = 2 * Dp * (d + 1) + 2 * h * Dp + 2 * Dp * h + 2 * h * d   # dPhi, dU, dW2, dW1
+    grad = BH * (n_q + n_k) * per_tok + BH * n_q * 2 * Dp * (d + 1)     # + dS_t, dz_t
+    return dict(forward=fwd["total"], gradient=grad, total=fwd["total"] + grad)
 
 
 def cpu_baseline(w, chunk, q, k, v, phi, heads, gpu_out):
@@ -88,12 +103,14 @@ def main():
     ap.add_argument("--workload", default="wan480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=12)
-    ap.add_argument("--mode", choices=("forward", "bidirectional", "stream", "fullsoftmax"),
+    ap.add_argument("--mode", choices=("forward", "bidirectional", "stream", "fullsoftmax", "backward"),
                     default="forward",
                     help="forward: rehyat_forward (the headline path); bidirectional: "
                          "rehyat_forward_ex(causal=0); stream: one rehyat_step per chunk with "
                          "caller-owned state and window; fullsoftmax: rehyat_forward with one "
-                         "chunk covering all frames (plain softmax attention, Eq. 2) on the same inputs")
+                         "chunk covering all frames (plain softmax attention, Eq. 2) on the same inputs; "
+                         "backward: rehyat_phi_backward (forward recomputation + gradients of the "
+                         "feature-map parameters, one distillation step of Eq. 19)")
     ap.add_argument("--overlap", type=int, default=0, help="T_o (bidirectional and stream modes)")
     ap.add_argument("--pmc-copy-mib", type=int, default=0,
                     help="after the timed steps also run one plain device-to-device copy of this "
@@ -124,6 +141,13 @@ def main():
     elif args.mode == "bidirectional":
         step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, chunk, out=out,
                                        overlap=overlap, causal=False)
+    elif args.mode == "backward":
+        dG = synth.make_grad_out(w.B, w.H, w.N, w.d).to("cuda", torch.bfloat16)
+        bws = torch.empty(binding.phi_backward_workspace_bytes(w.B, w.H, w.T, w.HW, w.d, chunk),
+                          device="cuda", dtype=torch.uint8)
+        grads = {n: torch.empty(t.shape, device="cuda", dtype=torch.float32) for n, t in dphi.items()}
+        step = lambda: binding.phi_backward(dq, dk, dv, dphi, dG, w.T, w.HW, chunk, workspace=bws,
+                                            out=out, grads=grads)
     else:
         # the caller's side of chunk-by-chunk generation: per chunk its queries, its K/V
         # window and the number of tokens that leave the window, prepared outside the timing
@@ -190,6 +214,23 @@ def main():
         del src, dst
 
     fl = algorithmic_flops(w, chunk, overlap, causal)
+    if args.mode == "backward":
+        # the library's per-kernel events cover forward calls only; rocprofv3 --kernel-trace
+        # gives this mode's kernel breakdown
+        bf = backward_flops(w, chunk, fl)
+        print(json.dumps({
+            "metric": "feature-map gradient step (forward recomputation + backward), tokens/s per layer",
+            "value": w.B * w.N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": ms, "ms_per_step_wall_mean": wall_ms,
+            "ms_per_step_min_max": [min(per_step), max(per_step)], "higher_is_better": True,
+            "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": f"{w.name}: B={w.B} H={w.H} d={w.d} T={w.T} HW={w.HW} N={w.N} "
+                                   f"chunk={chunk} causal row-max, rehyat_phi_backward"},
+            "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in bf.items()},
+            "tflops": bf["total"] / (ms * 1e-3) / 1e12,
+            "pct_mfma_peak": 100.0 * bf["total"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "workspace_bytes": int(bws.numel()), "library_version": binding.version()}))
+        return
     kern_ms = {kk: (tot / n if n else None) for kk, (tot, n) in prof.items()}
     # all launches of the attention kernel in one step share the step's algorithmic work
     attn_ms = prof["attn"][0] / args.steps

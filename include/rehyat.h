@@ -200,6 +200,54 @@ int rehyat_forward_noalloc(const void *q, const void *k, const void *v,
                            void *stream);
 
 /*
+ * Gradient of a loss with respect to the parameters of the two feature maps,
+ * for one step of the attention distillation of section 3.4 (Eq. 19), which
+ * trains phi_q and phi_k of a block and nothing else:
+ *     phi <- phi - eta * grad_phi E | y - y_hat |.
+ * The caller supplies G = dL/dy_hat (for the L1 loss of Eq. 19,
+ * sign(y_hat - y) / count); the call recomputes the forward pass (Eq. 5-9,
+ * causal sets of Eq. 13, stabiliser REHYAT_STAB_ROWMAX, under which the softmax
+ * terms do not depend on phi) and applies the chain rule through the linear
+ * terms (Eq. 7, 9, 14-18) and the two-layer map with its degree-2 polynomial
+ * features ("Characterization of phi").
+ *
+ *   q, k, v, phi_params, B, H, T, HW, d, chunk, overlap : as rehyat_forward_ex
+ *   grad_out  [B, H, N, d] bf16 DEVICE  G
+ *   out       [B, H, N, d] bf16 DEVICE, nullable: receives y_hat of the
+ *             recomputed forward pass
+ *   grads     HOST struct of DEVICE pointers, fp32, same shapes as the
+ *             parameters ([H, hidden, d], [H, hidden], [H, dprime, hidden],
+ *             [H, dprime] for each map), summed over the batch; overwritten
+ *   workspace DEVICE, 256-byte aligned, at least
+ *             rehyat_phi_backward_workspace_bytes(...) bytes.  Unlike the
+ *             forward workspace it grows with N: the hidden activations and
+ *             their gradients are kept token by token (about 2.3 KB per token
+ *             and head at d = 128).  Used only for the duration of the
+ *             enqueued work; no library state is touched.
+ *
+ * Sums over tokens run in a fixed order: results are bit-reproducible.
+ * Supported: d in {64, 128}, hidden = dprime = 2 d, degree 2, at most
+ * REHYAT_BACKWARD_MAX_CHUNKS chunks (else REHYAT_E_UNSUPPORTED), N below
+ * 2^31 / (4 d).  One chunk (chunk >= T) gives all-zero gradients.
+ * rehyat_phi_backward_workspace_bytes returns 0 for sizes the call rejects.
+ * Errors: as rehyat_forward_ex, plus REHYAT_E_NULL (grad_out, grads, one of its
+ * pointers, or workspace NULL) and REHYAT_E_WORKSPACE.
+ */
+#define REHYAT_BACKWARD_MAX_CHUNKS 1024
+typedef struct {
+  void *w1_q, *b1_q, *w2_q, *b2_q;
+  void *w1_k, *b1_k, *w2_k, *b2_k;
+} rehyat_phi_grads;
+size_t rehyat_phi_backward_workspace_bytes(int B, int H, int T, int HW, int d,
+                                           int chunk);
+int rehyat_phi_backward(const void *q, const void *k, const void *v,
+                        const rehyat_phi_params *phi_params,
+                        const void *grad_out, void *out,
+                        const rehyat_phi_grads *grads, int B, int H, int T,
+                        int HW, int d, int chunk, int overlap, void *workspace,
+                        size_t workspace_bytes, void *stream);
+
+/*
  * One step of the chunk-wise RNN (section 3.3, Eq. 14-18) for generation chunk by
  * chunk: the caller owns the state and the K/V window, the library holds nothing
  * between calls, and peak memory does not depend on how many chunks came before.

@@ -24,13 +24,34 @@ psi = relu(W2 u + b2), u = relu(W1 x + b1) ("Characterization of phi", appendix
 readings of the forward oracle; "parity unpinned" applies to them exactly as there.
 This function itself is pinned by central finite differences of the forward oracle
 (tests/test_oracle_grad_pins.py).
+
+ReLU gates are 0/1 decisions taken by floating point.  A kernel that keeps the hidden
+activations U in bf16 takes the second layer's gates (psi > 0) on slightly different
+values than fp64 does, and a gate that flips changes an entry of the gradient by its whole
+contribution, not by a rounding error.  `hidden_round="bf16"` makes this oracle take those
+decisions in the kernel's precision: U is rounded to the nearest-even bf16 value right after
+the first layer and everything downstream (forward and backward) uses the rounded U.  The
+default (None) is the exact fp64 chain that the finite-difference pins check; the option
+changes no formula, only the values of U.
 """
 import numpy as np
 
 
-def _mlp_forward(x, w1, b1, w2, b2):
+def round_to_bf16(x):
+    """Nearest-even bf16 value of each element (via fp32), returned as fp64."""
+    f = np.ascontiguousarray(x, dtype=np.float32)
+    bits = f.view(np.uint32).astype(np.uint64)
+    bits = (bits + 0x7FFF + ((bits >> 16) & 1)) & 0xFFFF0000
+    return bits.astype(np.uint32).view(np.float32).astype(np.float64).reshape(np.shape(x))
+
+
+def _mlp_forward(x, w1, b1, w2, b2, hidden_round=None):
     pre1 = x @ w1.T + b1
     u = np.maximum(pre1, 0.0)
+    if hidden_round == "bf16":
+        u = round_to_bf16(u)
+    elif hidden_round is not None:
+        raise ValueError("hidden_round must be None or 'bf16'")
     pre2 = u @ w2.T + b2
     psi = np.maximum(pre2, 0.0)
     half = psi.shape[1] // 2
@@ -65,7 +86,7 @@ def chunk_sets(T, HW, chunk, overlap):
     return rows
 
 
-def phi_backward(q, k, v, phi_params, G, T, HW, chunk, overlap=0):
+def phi_backward(q, k, v, phi_params, G, T, HW, chunk, overlap=0, hidden_round=None):
     """q, k, v, G: [B, H, N, d]; phi_params: dict of the eight tensors with a leading
     head axis.  Returns (grads dict of the same eight shapes, y_hat [B, H, N, d])."""
     q, k, v, G = (np.asarray(a, np.float64) for a in (q, k, v, G))
@@ -77,8 +98,8 @@ def phi_backward(q, k, v, phi_params, G, T, HW, chunk, overlap=0):
     sets = chunk_sets(T, HW, chunk, overlap)
     for b in range(B):
         for h in range(H):
-            uq, psiq, Fq = _mlp_forward(q[b, h], P["w1_q"][h], P["b1_q"][h], P["w2_q"][h], P["b2_q"][h])
-            uk, psik, Fk = _mlp_forward(k[b, h], P["w1_k"][h], P["b1_k"][h], P["w2_k"][h], P["b2_k"][h])
+            uq, psiq, Fq = _mlp_forward(q[b, h], P["w1_q"][h], P["b1_q"][h], P["w2_q"][h], P["b2_q"][h], hidden_round)
+            uk, psik, Fk = _mlp_forward(k[b, h], P["w1_k"][h], P["b1_k"][h], P["w2_k"][h], P["b2_k"][h], hidden_round)
             dFq = np.zeros_like(Fq)
             dFk = np.zeros_like(Fk)
             for (q_lo, q_hi, s_lo, s_hi, l_hi) in sets:

@@ -21,6 +21,7 @@ STAB_ROWMAX, STAB_NONE = 0, 1
 EXPORTS = ("rehyat_chunk_plan", "rehyat_workspace_bytes", "rehyat_set_workspace",
            "rehyat_forward", "rehyat_forward_ex", "rehyat_forward_ws", "rehyat_forward_noalloc",
            "rehyat_step", "rehyat_state", "rehyat_shutdown",
+           "rehyat_phi_backward", "rehyat_phi_backward_workspace_bytes",
            "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error",
            "rehyat_attn_kernel_name",
            "rehyat_profile_enable", "rehyat_profile_read")
@@ -35,6 +36,14 @@ class PhiParams(ctypes.Structure):
 
 class DebugOut(ctypes.Structure):
     _fields_ = [(n, ctypes.c_void_p) for n in ("m", "nS", "aS", "nL", "aL")]
+
+
+class PhiGrads(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("w1_q", "b1_q", "w2_q", "b2_q", "w1_k", "b1_k", "w2_k", "b2_k")]
+
+
+BACKWARD_MAX_CHUNKS = 1024
 
 
 class RehyatError(RuntimeError):
@@ -86,6 +95,12 @@ def _load():
     lib.rehyat_state.restype = ci
     lib.rehyat_state.argtypes = [vp, vp, ctypes.POINTER(PhiParams), vp, vp,
                                  ci, ci, ci, ci, ci, ci, vp]
+    lib.rehyat_phi_backward_workspace_bytes.restype = ctypes.c_size_t
+    lib.rehyat_phi_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    lib.rehyat_phi_backward.restype = ci
+    lib.rehyat_phi_backward.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp, vp,
+                                        ctypes.POINTER(PhiGrads), ci, ci, ci, ci, ci, ci, ci,
+                                        vp, ctypes.c_size_t, vp]
     lib.rehyat_shutdown.restype = ci
     lib.rehyat_shutdown.argtypes = []
     lib.rehyat_status_string.restype = ctypes.c_char_p
@@ -317,3 +332,52 @@ def state(k, v, phi, T, HW, upto_frames, stream=None):
     if rc != OK:
         raise RehyatError(rc, "rehyat_state")
     return S, z
+
+
+def phi_backward_workspace_bytes(B, H, T, HW, d, chunk):
+    return _load().rehyat_phi_backward_workspace_bytes(B, H, T, HW, d, chunk)
+
+
+def phi_backward(q, k, v, phi, grad_out, T, HW, chunk, overlap=0, workspace=None, out=None,
+                 grads=None, stream=None):
+    """Gradients of a loss w.r.t. the parameters of phi_q and phi_k for a given
+    ``grad_out`` = dL/dy_hat (CUDA bf16 [B, H, T*HW, d]): one step of the distillation of
+    Eq. 19.  Returns ``(grads, y_hat)``: a dict of eight fp32 CUDA tensors shaped like the
+    parameters, and the output of the recomputed forward pass.  ``workspace`` is a CUDA
+    byte tensor of at least ``phi_backward_workspace_bytes`` bytes (allocated here if
+    None)."""
+    lib = _load()
+    _check_qkv(q, k, v)
+    if grad_out.shape != q.shape or grad_out.dtype != torch.bfloat16 or not grad_out.is_cuda \
+            or not grad_out.is_contiguous():
+        raise TypeError("grad_out must be a contiguous CUDA bf16 tensor shaped like q")
+    B, H, N, d = q.shape
+    if N != T * HW:
+        raise ValueError("N != T*HW")
+    p, Hp = _phi_struct(phi, d)
+    if Hp != H:
+        raise ValueError("phi head count differs from q")
+    if workspace is None:
+        need = lib.rehyat_phi_backward_workspace_bytes(B, H, T, HW, d, chunk)
+        if need == 0:
+            raise RehyatError(E_UNSUPPORTED, "rehyat_phi_backward_workspace_bytes")
+        workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+    if out is None:
+        out = torch.empty_like(q)
+    if grads is None:
+        grads = {n: torch.empty(t.shape, device=q.device, dtype=torch.float32) for n, t in phi.items()}
+    g = PhiGrads()
+    for name in ("w1_q", "b1_q", "w2_q", "b2_q", "w1_k", "b1_k", "w2_k", "b2_k"):
+        t = grads[name]
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.shape != phi[name].shape:
+            raise TypeError(f"grads[{name}] must be a contiguous CUDA fp32 tensor shaped like phi[{name}]")
+        setattr(g, name, t.data_ptr())
+    s = torch.cuda.current_stream() if stream is None else stream
+    rc = lib.rehyat_phi_backward(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(p),
+                                 grad_out.data_ptr(), out.data_ptr(), ctypes.byref(g),
+                                 B, H, T, HW, d, chunk, overlap, workspace.data_ptr(),
+                                 workspace.numel() * workspace.element_size(),
+                                 ctypes.c_void_p(s.cuda_stream))
+    if rc != OK:
+        raise RehyatError(rc, "rehyat_phi_backward")
+    return grads, out

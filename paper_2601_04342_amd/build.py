@@ -6,7 +6,8 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librehyat.so")
-SOURCES = ["rehyat_api.hip", "rehyat_state.hip", "rehyat_prefix.hip", "rehyat_attn.hip"]
+SOURCES = ["rehyat_api.hip", "rehyat_state.hip", "rehyat_prefix.hip", "rehyat_attn.hip",
+           "rehyat_grad.hip"]
 HEADERS = ["rehyat_device.h", "rehyat_kernels.h"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

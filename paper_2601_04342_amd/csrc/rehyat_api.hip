@@ -207,6 +207,7 @@ int launch_state_window(const Ctx& c, const void* k, const void* v, const rehyat
   s.items_per_xcd = (s.n_items + 7) / 8;
   s.kv_bh_stride = (int64_t)T * HW * d;
   s.step_n = 0;
+  s.query_segments = 0;
   ProfScope prof(c.prof, 0, c.st);
   hipError_t e = launch_state(s, d, s.items_per_xcd * 8, c.st);
   if (e != hipSuccess) return hip_fail(e, "state kernel launch");
@@ -420,6 +421,173 @@ int forward_core(const Ctx& c, const void* q, const void* k, const void* v,
   return REHYAT_OK;
 }
 
+// ---- feature-map gradient (Eq. 19): workspace plan and launches ----------------------
+struct BwdPlan {
+  Slots sl;          // forward areas: one window holds every chunk
+  WsLayout F;
+  int nc, n_seg;     // chunks; segments (= chunks that read a state)
+  int nsplit;        // pieces per segment (state and activation-gradient kernels)
+  int nsplit_g;      // pieces per (b, h) of the weight-gradient kernels
+  size_t yhat, nS, nL, u, tokw, Sn, Rt, Rn, rz, w2t_q, w2t_k, U, dpsi, p_w2, p_w1, p_b2, p_dz, total;
+};
+
+BwdPlan bwd_plan(int B, int H, int T, int HW, int d, int chunk) {
+  BwdPlan P;
+  const int dp = 2 * d, hid = 2 * d;
+  const size_t BH = (size_t)B * H, N = (size_t)T * HW;
+  P.nc = num_chunks(T, chunk);
+  P.n_seg = P.nc > 1 ? P.nc - 1 : 1;
+  P.nsplit = choose_nsplit((int)BH, P.n_seg, Slots{kMaxSplit * P.nc, P.nc});
+  P.sl = Slots{P.n_seg * P.nsplit, P.nc};
+  P.F = ws_layout(B, H, d, dp, P.sl);
+  // weight-gradient kernels: one (b, h) token range cut so that the pieces about fill the chip
+  int ns = (int)(kCUs / BH);
+  if (ns < 1) ns = 1;
+  const size_t tiles = (N + 63) / 64;
+  if ((size_t)ns > tiles) ns = (int)tiles;
+  P.nsplit_g = ns;
+  size_t off = P.F.total;
+  auto take = [&](size_t bytes) {
+    const size_t o = off;
+    off += align256(bytes);
+    return o;
+  };
+  P.yhat = take(BH * N * d * sizeof(bf16_t));
+  P.nS = take(BH * N * sizeof(float));
+  P.nL = take(BH * N * sizeof(float));
+  P.u = take(BH * N * d * sizeof(bf16_t));
+  P.tokw = take(BH * N * sizeof(float));
+  P.Sn = take(BH * P.nc * (size_t)dp * d * sizeof(bf16_t));
+  P.Rt = take(BH * P.nc * (size_t)dp * d * sizeof(bf16_t));
+  P.Rn = take(BH * P.nc * (size_t)dp * d * sizeof(bf16_t));
+  P.rz = take(BH * P.nc * (size_t)dp * sizeof(float));
+  P.w2t_q = take((size_t)H * hid * dp * sizeof(bf16_t));
+  P.w2t_k = take((size_t)H * hid * dp * sizeof(bf16_t));
+  P.U = take(BH * N * hid * sizeof(bf16_t));
+  P.dpsi = take(BH * N * dp * sizeof(bf16_t));
+  P.p_w2 = take(BH * ns * (size_t)dp * hid * sizeof(float));
+  P.p_w1 = take(BH * ns * ((size_t)d * hid + hid) * sizeof(float));
+  P.p_b2 = take(BH * P.n_seg * P.nsplit * (size_t)dp * sizeof(float));
+  P.p_dz = take(BH * P.n_seg * P.nsplit * (size_t)dp * sizeof(float));
+  P.total = off;
+  return P;
+}
+
+struct SideParams {   // one feature map and where its gradients go
+  const void *w1, *b1, *w2, *b2;
+  float *g_w1, *g_b1, *g_w2, *g_b2;
+};
+
+// Activation gradients, then the weight gradients, of one side.  `x` is q or k, `vec` is u or
+// v, `M`/`zv` the per-segment matrices of dPhi = M vec + tokw zv; [lo, hi) is the token range
+// of every (b, h) that the segments cover.
+int backward_side(char* ws, const BwdPlan& P, hipStream_t st, const void* x, const void* vec,
+                  const float* tokw, const SideParams& sp, const bf16_t* w2t, const bf16_t* M,
+                  const float* zv, bool query_side, float* dz_part, int B, int H, int T, int HW,
+                  int d, int chunk, int overlap, int64_t lo, int64_t hi) {
+  const int dp = 2 * d, hid = 2 * d;
+  const int BH = B * H;
+  ActGradArgs g;
+  g.x = (const bf16_t*)x;
+  g.vec = (const bf16_t*)vec;
+  g.tokw = tokw;
+  g.w1 = (const bf16_t*)sp.w1;
+  g.b1 = (const float*)sp.b1;
+  g.w2 = (const bf16_t*)sp.w2;
+  g.b2 = (const float*)sp.b2;
+  g.M = M;
+  g.zv = zv;
+  g.U = (bf16_t*)(ws + P.U);
+  g.dpsi = (bf16_t*)(ws + P.dpsi);
+  g.db2_part = (float*)(ws + P.p_b2);
+  g.dz_part = dz_part;
+  g.H = H;
+  g.T = T;
+  g.HW = HW;
+  g.chunk = chunk;
+  g.overlap = overlap;
+  g.query_side = query_side ? 1 : 0;
+  g.n_seg = P.n_seg;
+  g.nsplit = P.nsplit;
+  g.slots = P.nc;
+  g.n_items = BH * P.n_seg * P.nsplit;
+  g.items_per_xcd = (g.n_items + 7) / 8;
+  hipError_t e = launch_act_grad(g, d, g.items_per_xcd * 8, st);
+  if (e != hipSuccess) return hip_fail(e, "activation-gradient kernel launch");
+
+  ReduceArgs r;
+  r.B = B;
+  r.H = H;
+  r.part = (const float*)(ws + P.p_b2);
+  r.out = sp.g_b2;
+  r.per_bh = P.n_seg * P.nsplit;
+  r.part_stride = dp;
+  r.part_off = 0;
+  r.R = 1;
+  r.C = dp;
+  r.transpose = 0;
+  e = launch_reduce(r, st);
+  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
+
+  const int n_items = BH * P.nsplit_g;
+  TnGemmArgs t;
+  t.X = (const bf16_t*)(ws + P.dpsi);
+  t.Y = (const bf16_t*)(ws + P.U);
+  t.part = (float*)(ws + P.p_w2);
+  t.N = (int64_t)T * HW;
+  t.lo = lo;
+  t.hi = hi;
+  t.nsplit = P.nsplit_g;
+  t.n_items = n_items;
+  t.items_per_xcd = (n_items + 7) / 8;
+  e = launch_tn_gemm(t, d, t.items_per_xcd * 8, st);
+  if (e != hipSuccess) return hip_fail(e, "second-layer gradient kernel launch");
+  r.part = (const float*)(ws + P.p_w2);
+  r.out = sp.g_w2;
+  r.per_bh = P.nsplit_g;
+  r.part_stride = (int64_t)dp * hid;
+  r.part_off = 0;
+  r.R = dp;
+  r.C = hid;
+  r.transpose = 0;
+  e = launch_reduce(r, st);
+  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
+
+  HidGradArgs hg;
+  hg.dpsi = (const bf16_t*)(ws + P.dpsi);
+  hg.U = (const bf16_t*)(ws + P.U);
+  hg.x = (const bf16_t*)x;
+  hg.w2t = w2t;
+  hg.part = (float*)(ws + P.p_w1);
+  hg.H = H;
+  hg.N = (int64_t)T * HW;
+  hg.lo = lo;
+  hg.hi = hi;
+  hg.nsplit = P.nsplit_g;
+  hg.n_items = n_items;
+  hg.items_per_xcd = (n_items + 7) / 8;
+  e = launch_hid_grad(hg, d, hg.items_per_xcd * 8, st);
+  if (e != hipSuccess) return hip_fail(e, "first-layer gradient kernel launch");
+  r.part = (const float*)(ws + P.p_w1);
+  r.per_bh = P.nsplit_g;
+  r.part_stride = (int64_t)d * hid + hid;
+  r.out = sp.g_w1;   // partial is dW1^T [d][hidden]
+  r.part_off = 0;
+  r.R = d;
+  r.C = hid;
+  r.transpose = 1;
+  e = launch_reduce(r, st);
+  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
+  r.out = sp.g_b1;
+  r.part_off = (int64_t)d * hid;
+  r.R = 1;
+  r.C = hid;
+  r.transpose = 0;
+  e = launch_reduce(r, st);
+  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
+  return REHYAT_OK;
+}
+
 // Largest slot counts whose layout fits `bytes` (equal partial and state slots, at most the
 // default window); 0 slots when not even one fits.
 Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
@@ -436,7 +604,7 @@ Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
 
 extern "C" {
 
-int rehyat_version(void) { return 210; }
+int rehyat_version(void) { return 300; }
 
 const char* rehyat_status_string(int code) {
   switch (code) {
@@ -575,6 +743,189 @@ int rehyat_forward_noalloc(const void* q, const void* k, const void* v, const re
                       REHYAT_STAB_ROWMAX);
 }
 
+size_t rehyat_phi_backward_workspace_bytes(int B, int H, int T, int HW, int d, int chunk) {
+  if (B < 1 || H < 1 || T < 1 || HW < 1 || chunk < 1 || (d != 64 && d != 128)) return 0;
+  if ((int64_t)T * HW >= ((int64_t)1 << 31) / (4 * d) || (int64_t)B * H > 65535) return 0;
+  if (chunk > T) chunk = T;
+  if (num_chunks(T, chunk) > REHYAT_BACKWARD_MAX_CHUNKS) return 0;
+  return bwd_plan(B, H, T, HW, d, chunk).total;
+}
+
+int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
+                        const void* grad_out, void* out, const rehyat_phi_grads* grads, int B,
+                        int H, int T, int HW, int d, int chunk, int overlap, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+  if (!grad_out || !grads) return REHYAT_E_NULL;
+  int rc = validate_forward(q, k, v, phi, out ? out : grad_out, B, H, T, HW, d, &chunk, &overlap, 1,
+                            REHYAT_STAB_ROWMAX);
+  if (rc != REHYAT_OK) return rc;
+  if (!grads->w1_q || !grads->b1_q || !grads->w2_q || !grads->b2_q || !grads->w1_k ||
+      !grads->b1_k || !grads->w2_k || !grads->b2_k)
+    return REHYAT_E_NULL;
+  if (!aligned16(grad_out)) return REHYAT_E_SHAPE;
+  if (!aligned4(grads->w1_q) || !aligned4(grads->b1_q) || !aligned4(grads->w2_q) ||
+      !aligned4(grads->b2_q) || !aligned4(grads->w1_k) || !aligned4(grads->b1_k) ||
+      !aligned4(grads->w2_k) || !aligned4(grads->b2_k))
+    return REHYAT_E_SHAPE;
+  // tile offsets of the token-major activation buffers (rows of 4 d bytes) are 32-bit
+  if ((int64_t)T * HW >= ((int64_t)1 << 31) / (4 * d)) return REHYAT_E_SHAPE;
+  const int nc = num_chunks(T, chunk);
+  if (nc > REHYAT_BACKWARD_MAX_CHUNKS) return REHYAT_E_UNSUPPORTED;
+  // every chunk goes into one launch: its workgroup count must fit an int
+  if ((int64_t)B * H * nc * (((int64_t)chunk * HW + 63) / 64) >= ((int64_t)1 << 31)) return REHYAT_E_SHAPE;
+  if (!workspace) return REHYAT_E_NULL;
+  const BwdPlan P = bwd_plan(B, H, T, HW, d, chunk);
+  if ((((uintptr_t)workspace) & 255) || workspace_bytes < P.total) return REHYAT_E_WORKSPACE;
+  char* ws = (char*)workspace;
+  hipStream_t st = (hipStream_t)stream;
+  const int dp = 2 * d, hid = 2 * d;
+  const int BH = B * H;
+  const int64_t N = (int64_t)T * HW;
+  void* y = out ? out : (void*)(ws + P.yhat);
+
+  Ctx c;
+  c.ws = ws;
+  c.L = P.F;
+  c.sl = P.sl;
+  c.st = st;
+  c.prof = false;
+  const int qtile = attn_query_tile(d);
+  const int qtiles = (int)(((int64_t)chunk * HW + qtile - 1) / qtile);
+
+  if (nc == 1) {
+    // one chunk: plain softmax attention (Eq. 2), independent of phi -- all gradients are zero
+    rc = launch_attn_window(c, q, k, v, phi, y, nullptr, B, H, T, HW, d, chunk, overlap, 0, 1, qtiles,
+                            REHYAT_STAB_ROWMAX, false);
+    if (rc != REHYAT_OK) return rc;
+    float* gp[8] = {(float*)grads->w1_q, (float*)grads->b1_q, (float*)grads->w2_q, (float*)grads->b2_q,
+                    (float*)grads->w1_k, (float*)grads->b1_k, (float*)grads->w2_k, (float*)grads->b2_k};
+    const int64_t gn[4] = {(int64_t)H * hid * d, (int64_t)H * hid, (int64_t)H * dp * hid, (int64_t)H * dp};
+    for (int i = 0; i < 8; ++i) {
+      hipError_t e = launch_fill_zero(gp[i], gn[i % 4], st);
+      if (e != hipSuccess) return hip_fail(e, "fill kernel launch");
+    }
+    return REHYAT_OK;
+  }
+
+  // ---- forward pass, every chunk state kept (one window) ----------------------------
+  rc = launch_state_window(c, k, v, phi, B, H, T, HW, d, chunk, overlap, 0, P.n_seg, P.nsplit);
+  if (rc != REHYAT_OK) return rc;
+  rc = launch_prefix_window(c, B, H, d, dp, nc, P.n_seg, P.nsplit, true);
+  if (rc != REHYAT_OK) return rc;
+  rehyat_debug_out dbg;
+  dbg.m = dbg.aS = dbg.aL = nullptr;
+  dbg.nS = (float*)(ws + P.nS);
+  dbg.nL = (float*)(ws + P.nL);
+  rc = launch_attn_window(c, q, k, v, phi, y, &dbg, B, H, T, HW, d, chunk, overlap, 0, nc, qtiles,
+                          REHYAT_STAB_ROWMAX, false);
+  if (rc != REHYAT_OK) return rc;
+
+  hipError_t e;
+  TransposeArgs tr;
+  tr.in = (const bf16_t*)(ws + P.F.state_s);   // S_t^T [d][dp] -> S_t [dp][d]
+  tr.out = (bf16_t*)(ws + P.Sn);
+  tr.n = BH * nc;
+  tr.R = d;
+  tr.C = dp;
+  e = launch_transpose(tr, st);
+  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
+  tr.n = H;   // W2 [dp][hidden] -> [hidden][dp]
+  tr.R = dp;
+  tr.C = hid;
+  tr.in = (const bf16_t*)phi->w2_q;
+  tr.out = (bf16_t*)(ws + P.w2t_q);
+  e = launch_transpose(tr, st);
+  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
+  tr.in = (const bf16_t*)phi->w2_k;
+  tr.out = (bf16_t*)(ws + P.w2t_k);
+  e = launch_transpose(tr, st);
+  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
+
+  // ---- u, w per token ---------------------------------------------------------------
+  PrepArgs pa;
+  pa.g = (const bf16_t*)grad_out;
+  pa.y = (const bf16_t*)y;
+  pa.nS = (const float*)(ws + P.nS);
+  pa.nL = (const float*)(ws + P.nL);
+  pa.u = (bf16_t*)(ws + P.u);
+  pa.tokw = (float*)(ws + P.tokw);
+  pa.tokens = (int64_t)BH * N;
+  pa.d = d;
+  e = launch_prep(pa, st);
+  if (e != hipSuccess) return hip_fail(e, "gradient preparation kernel launch");
+
+  // ---- dL/dS_t partial sums: the chunk-state kernel on (q, u) with phi_q, query segments ---
+  {
+    StateArgs s;
+    s.k = (const bf16_t*)q;
+    s.v = (const bf16_t*)(ws + P.u);
+    s.w1_k = (const bf16_t*)phi->w1_q;
+    s.b1_k = (const float*)phi->b1_q;
+    s.w2_k = (const bf16_t*)phi->w2_q;
+    s.b2_k = (const float*)phi->b2_q;
+    s.partial = (float*)(ws + P.F.partial);
+    s.H = H;
+    s.T = T;
+    s.HW = HW;
+    s.chunk = chunk;
+    s.overlap = overlap;
+    s.chunk0 = 1;
+    s.n_seg = P.n_seg;
+    s.nsplit = P.nsplit;
+    s.partial_slots = P.sl.partial;
+    s.n_items = BH * P.n_seg * P.nsplit;
+    s.items_per_xcd = (s.n_items + 7) / 8;
+    s.kv_bh_stride = N * d;
+    s.step_n = 0;
+    s.query_segments = 1;
+    e = launch_state(s, d, s.items_per_xcd * 8, st);
+    if (e != hipSuccess) return hip_fail(e, "state-gradient kernel launch");
+  }
+
+  // ---- query side ----------------------------------------------------------------------
+  SideParams sq{phi->w1_q, phi->b1_q, phi->w2_q, phi->b2_q,
+                (float*)grads->w1_q, (float*)grads->b1_q, (float*)grads->w2_q, (float*)grads->b2_q};
+  const ChunkRange c1 = chunk_range(T, HW, chunk, overlap, 1);
+  rc = backward_side(ws, P, st, q, ws + P.u, (const float*)(ws + P.tokw), sq,
+                     (const bf16_t*)(ws + P.w2t_q), (const bf16_t*)(ws + P.Sn),
+                     (const float*)(ws + P.F.state_z), true, (float*)(ws + P.p_dz), B, H, T, HW, d,
+                     chunk, overlap, c1.q_lo, N);
+  if (rc != REHYAT_OK) return rc;
+
+  // ---- R_tau, r_tau ------------------------------------------------------------------
+  SuffixArgs sa;
+  sa.s_part = (const float*)(ws + P.F.partial);
+  sa.z_part = (const float*)(ws + P.p_dz);
+  sa.Rt = (bf16_t*)(ws + P.Rt);
+  sa.r = (float*)(ws + P.rz);
+  sa.BH = BH;
+  sa.n_seg = P.n_seg;
+  sa.s_nsplit = P.nsplit;
+  sa.s_slots = P.sl.partial;
+  sa.z_nsplit = P.nsplit;
+  sa.slots = nc;
+  sa.elems = d * dp + dp;
+  sa.s_elems = d * dp;
+  sa.dp = dp;
+  e = launch_suffix(sa, st);
+  if (e != hipSuccess) return hip_fail(e, "suffix kernel launch");
+  tr.in = (const bf16_t*)(ws + P.Rt);
+  tr.out = (bf16_t*)(ws + P.Rn);
+  tr.n = BH * nc;
+  tr.R = d;
+  tr.C = dp;
+  e = launch_transpose(tr, st);
+  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
+
+  // ---- key side ------------------------------------------------------------------------
+  SideParams sk{phi->w1_k, phi->b1_k, phi->w2_k, phi->b2_k,
+                (float*)grads->w1_k, (float*)grads->b1_k, (float*)grads->w2_k, (float*)grads->b2_k};
+  const ChunkRange cl = chunk_range(T, HW, chunk, overlap, nc - 1);
+  return backward_side(ws, P, st, k, v, nullptr, sk, (const bf16_t*)(ws + P.w2t_k),
+                       (const bf16_t*)(ws + P.Rn), (const float*)(ws + P.rz), false, nullptr, B, H, T,
+                       HW, d, chunk, overlap, 0, cl.s_lo);
+}
+
 int rehyat_profile_enable(int on) {
   std::lock_guard<std::mutex> lock(g_mu);
   g_prof.on = on != 0;
@@ -678,6 +1029,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
     s.items_per_xcd = (s.n_items + 7) / 8;
     s.kv_bh_stride = (int64_t)n_win * d;
     s.step_n = n_absorb;
+    s.query_segments = 0;
     ProfScope prof(true, 0, st);
     e = launch_state(s, d, s.items_per_xcd * 8, st);
     if (e != hipSuccess) return hip_fail(e, "state kernel launch");

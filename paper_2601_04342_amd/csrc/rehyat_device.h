@@ -107,7 +107,9 @@ __device__ __forceinline__ i16x4 lds_read_tr(const bf16_t* p) {
 // ---------------------------------------------------------------------------
 template <int ROWBYTES>
 __device__ __forceinline__ int swz(int row) {
-  if (ROWBYTES == 256) return ((row & 3) << 2) | ((row >> 2) & 3);   // 16 chunks per row
+  // 256- and 512-byte rows: 16 consecutive rows land on 16 distinct chunk positions (the
+  // permutation touches the low four bits of the chunk index only)
+  if (ROWBYTES == 256 || ROWBYTES == 512) return ((row & 3) << 2) | ((row >> 2) & 3);
   return (((row >> 1) & 1) << 2) | ((row >> 2) & 3);                  // 128-byte rows, 8 chunks
 }
 
@@ -226,6 +228,11 @@ __device__ __forceinline__ void tile_load_asm(u32x4 rsrc, int soff, uint32_t lds
 template <int N>
 __device__ __forceinline__ void wait_loads_and_barrier() {
   asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+// Wait for this wave's LDS accesses only, then workgroup barrier (outstanding global
+// stores and loads stay in flight).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 __device__ __forceinline__ bf16x8 join_tr(i16x4 lo, i16x4 hi) {
   typedef __attribute__((__vector_size__(8 * sizeof(short)))) short i16x8;

@@ -1,0 +1,651 @@
+// Kernels of the feature-map gradient for gfx950: dL/d(phi_q, phi_k parameters) for a given
+// dL/dy_hat -- what one step of the attention distillation of section 3.4 (Eq. 19) needs,
+// which trains nothing but the two feature maps of a block.
+//
+// With the per-row stabiliser the softmax terms of Eq. 5 do not depend on phi, so the
+// chain rule runs through the linear terms only (Eq. 7, 9, 16):
+//   u_i = G_i / den_i,  w_i = -(G_i . y_i) / den_i,  den_i = n^S_i + n^L_i
+//   dL/dPhi_q,i = S_t u_i + w_i z_t
+//   dL/dS_t = sum_i Phi_q,i u_i^T,  dL/dz_t = sum_i w_i Phi_q,i           (queries i of chunk t)
+//   dL/dPhi_k,j = R_tau v_j + r_tau,  R_tau = sum_{t > tau} dL/dS_t        (keys j of segment tau)
+// and then through phi = [psi_1, psi_2^2], psi = relu(W2 U + b2), U = relu(W1 x + b1).
+//
+// Kernels, in launch order for one side (queries, then keys):
+//   prep_kernel       u, w per token (HBM-bound)
+//   state_kernel      (rehyat_state.hip, query segments) dL/dS_t partial sums
+//   act_grad_kernel   recomputes U and psi, forms dPhi and dpsi per token; writes U and dpsi
+//                     token-major, and the partial sums of db2 and dL/dz_t
+//   suffix_kernel     R_tau, r_tau from the partial sums
+//   tn_gemm_kernel    dW2 = dpsi^T U over tokens
+//   hid_grad_kernel   dU = (dpsi W2) [U > 0]; dW1 = dU^T x, db1 = sum dU
+//   reduce_kernel     sums the per-workgroup partials over batch and pieces
+// The contraction kernels follow the chunk-state kernel's scheme: wave w owns 32 hidden
+// units or features, weights of its slice live in registers as MFMA B operands, tiles of 64
+// tokens arrive by direct global->LDS loads, products are computed with tokens in the
+// accumulator rows so that an accumulator is directly the B operand of the token
+// contraction that follows.
+#include <type_traits>
+
+#include "rehyat_device.h"
+#include "rehyat_kernels.h"
+
+namespace rehyat {
+
+// ------------------------------------------------------------------------------------
+// u_i = G_i / den_i (bf16), w_i = -(G_i . y_i) / den_i.  Eight elements per thread, D/8
+// consecutive lanes per token.
+// ------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256)
+prep_kernel(PrepArgs a) {
+  constexpr int LPT = D / 8;  // lanes per token
+  const int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  int64_t tok = gid / LPT;
+  const int part = (int)(gid % LPT);
+  const bool live = tok < a.tokens;
+  if (!live) tok = a.tokens - 1;  // keep the lane in the shuffles below
+  const int64_t off = tok * D + 8 * part;
+  const u32x4 gr = *reinterpret_cast<const u32x4*>(a.g + off);
+  const u32x4 yr = *reinterpret_cast<const u32x4*>(a.y + off);
+  const float inv = 1.0f / (a.nS[tok] + a.nL[tok]);
+  float dot = 0.f;
+  u32x4 ur;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const float g0 = __builtin_bit_cast(float, gr[i] << 16), g1 = __builtin_bit_cast(float, gr[i] & 0xffff0000u);
+    const float y0 = __builtin_bit_cast(float, yr[i] << 16), y1 = __builtin_bit_cast(float, yr[i] & 0xffff0000u);
+    dot += g0 * y0 + g1 * y1;
+    ur[i] = pack_bf16(g0 * inv, g1 * inv);
+  }
+#pragma unroll
+  for (int m = 1; m < LPT; m <<= 1) dot += __shfl_xor(dot, m);
+  if (live) {
+    *reinterpret_cast<u32x4*>(a.u + off) = ur;
+    if (part == 0) a.tokw[tok] = -dot * inv;
+  }
+}
+
+hipError_t launch_prep(const PrepArgs& a, hipStream_t stream) {
+  const int lpt = a.d / 8;
+  const int64_t threads = a.tokens * lpt;
+  const unsigned grid = (unsigned)((threads + 255) / 256);
+  if (a.d == 128) hipLaunchKernelGGL(prep_kernel<128>, dim3(grid), dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(prep_kernel<64>, dim3(grid), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// R_tau = sum over segments s >= tau of the chunk-state gradient partials (segment s holds
+// dL/dS of chunk s+1, so this is the sum over chunks t > tau), r_tau likewise.  Each thread
+// owns four consecutive elements and walks the segments from the last to the first (fixed
+// order: bit-reproducible).
+// ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+suffix_kernel(SuffixArgs a) {
+  const int bh = blockIdx.y;
+  const int idx = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (idx >= a.elems) return;
+  const bool is_s = idx < a.s_elems;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  for (int c = a.n_seg - 1; c >= 0; --c) {
+    if (is_s) {
+      const float* p = a.s_part + ((int64_t)bh * a.s_slots + (int64_t)c * a.s_nsplit) * a.elems + idx;
+      for (int sp = 0; sp < a.s_nsplit; ++sp) acc += *reinterpret_cast<const f32x4*>(p + (int64_t)sp * a.elems);
+      u32x2 pk;
+      pk[0] = pack_bf16(acc[0], acc[1]);
+      pk[1] = pack_bf16(acc[2], acc[3]);
+      *reinterpret_cast<u32x2*>(a.Rt + ((int64_t)bh * a.slots + c) * a.s_elems + idx) = pk;
+    } else {
+      const int zi = idx - a.s_elems;
+      const float* p = a.z_part + (((int64_t)bh * a.n_seg + c) * a.z_nsplit) * a.dp + zi;
+      for (int sp = 0; sp < a.z_nsplit; ++sp) acc += *reinterpret_cast<const f32x4*>(p + (int64_t)sp * a.dp);
+      *reinterpret_cast<f32x4*>(a.r + ((int64_t)bh * a.slots + c) * a.dp + zi) = acc;
+    }
+  }
+}
+
+hipError_t launch_suffix(const SuffixArgs& a, hipStream_t stream) {
+  dim3 grid((a.elems / 4 + 255) / 256, a.BH);
+  hipLaunchKernelGGL(suffix_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// bf16 [n][R][C] -> [n][C][R] through a padded 32 x 32 LDS tile.
+// ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+transpose_kernel(TransposeArgs a) {
+  __shared__ bf16_t tile[32][33];
+  const int m = blockIdx.z;
+  const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  const bf16_t* in = a.in + (int64_t)m * a.R * a.C;
+  bf16_t* out = a.out + (int64_t)m * a.R * a.C;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int rr = r0 + ty + 8 * j, cc = c0 + tx;
+    if (rr < a.R && cc < a.C) tile[ty + 8 * j][tx] = in[(int64_t)rr * a.C + cc];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int cc = c0 + ty + 8 * j, rr = r0 + tx;
+    if (rr < a.R && cc < a.C) out[(int64_t)cc * a.R + rr] = tile[tx][ty + 8 * j];
+  }
+}
+
+hipError_t launch_transpose(const TransposeArgs& a, hipStream_t stream) {
+  dim3 grid((a.C + 31) / 32, (a.R + 31) / 32, a.n);
+  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// Activation gradients.  Per tile of 64 tokens:
+//   first half   U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden]
+//                (as in the chunk-state kernel), and from there to HBM;
+//   second half  psi slice = U W2[slice]^T + b2 and dPhi slice = Vec M[slice]^T, both with
+//                tokens in accumulator rows and the wave's 32 features in lanes;
+//                dpsi = dPhi + w zv, times 2 psi in the squared half, zero where psi = 0.
+// ------------------------------------------------------------------------------------
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW)
+act_grad_kernel(ActGradArgs a) {
+  constexpr int HID = 2 * D, DP = 2 * D;
+  constexpr int KS = D / 16;
+  constexpr int KS2 = HID / 16;
+  constexpr int NT = 64 * NW;
+  constexpr int TB = 64 * 2 * D;  // bytes of an x, vec or W1 tile
+  constexpr int UROW = HID * 2;
+  static_assert(DP / NW == 32, "each wave owns 32 features");
+
+  __shared__ __attribute__((aligned(1024))) char W1s[(HID / 64) * TB];
+  __shared__ __attribute__((aligned(1024))) char Xs[TB];
+  __shared__ __attribute__((aligned(1024))) char Vs[TB];
+  __shared__ __attribute__((aligned(1024))) char Us[64 * UROW];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5;
+  const int r = lane & 31;
+
+  const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);
+  if (item >= a.n_items) return;
+  const int sp = item % a.nsplit;
+  const int rest = item / a.nsplit;
+  const int seg = rest % a.n_seg;
+  const int bh = rest / a.n_seg;
+  const int h = bh % a.H;
+
+  int64_t seg_lo, seg_hi;
+  int slot;
+  if (a.query_side) {
+    const ChunkRange cr = chunk_range(a.T, a.HW, a.chunk, a.overlap, seg + 1);
+    seg_lo = cr.q_lo;
+    seg_hi = cr.q_hi;
+    slot = seg + 1;
+  } else {  // keys that enter the linear set between chunk seg and chunk seg + 1 (Eq. 13)
+    seg_lo = chunk_range(a.T, a.HW, a.chunk, a.overlap, seg).s_lo;
+    seg_hi = chunk_range(a.T, a.HW, a.chunk, a.overlap, seg + 1).s_lo;
+    slot = seg;
+  }
+  const int64_t N = (int64_t)a.T * a.HW;
+  const int64_t len = seg_hi - seg_lo;
+  const int64_t lo = seg_lo + (len * sp) / a.nsplit;
+  const int64_t hi = seg_lo + (len * (sp + 1)) / a.nsplit;
+  const int n_full = (int)((hi - lo) / 64);
+  const int rem = (int)((hi - lo) - 64 * (int64_t)n_full);
+  const int n_tiles = n_full + (rem > 0 ? 1 : 0);
+
+  const int64_t row0 = (int64_t)bh * N + lo;  // first token of this piece, over all (b, h)
+  const char* Xb = reinterpret_cast<const char*>(a.x + row0 * D);
+  const char* Vb = reinterpret_cast<const char*>(a.vec + row0 * D);
+  const char* W1 = reinterpret_cast<const char*>(a.w1 + (int64_t)h * HID * D);
+  const bf16_t* W2 = a.w2 + (int64_t)h * DP * HID;
+  char* Ug = reinterpret_cast<char*>(a.U + row0 * HID);
+  bf16_t* Pg = a.dpsi + row0 * DP;
+  const float* Tw = a.tokw ? a.tokw + row0 : nullptr;
+
+  // ---- resident operands ----------------------------------------------------
+  float b1lo[16], b1hi[16];
+  {
+    const float* bp = a.b1 + (int64_t)h * HID + wave * 32;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        b1lo[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + j])));
+        b1hi[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + 4 + j])));
+      }
+  }
+  const int unit = wave * 32 + r;  // this lane's feature
+  const float b2v = a.b2[(int64_t)h * DP + unit];
+  const float zvv = a.zv[((int64_t)bh * a.slots + slot) * DP + unit];
+  bf16x8 w2f[KS2];  // B operands: column = feature, k = hidden
+  {
+    const bf16_t* p = W2 + (int64_t)unit * HID + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS2; ++ks) w2f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
+  bf16x8 mf[KS];    // B operands: column = feature, k = head dimension (row `unit` of M)
+  {
+    const bf16_t* p = a.M + (((int64_t)bh * a.slots + slot) * DP + unit) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) mf[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
+
+  const u32x4 Xr = make_rsrc_words(Xb), Vr = make_rsrc_words(Vb), W1r = make_rsrc_words(W1);
+#pragma unroll
+  for (int j = 0; j < HID / 64; ++j)
+    tile_load_asm<2 * D, TB, NW>(W1r, j * TB, lds_address(W1s) + j * TB, wave, lane, 64);
+
+  // ---- per-lane LDS byte offsets (as in the chunk-state kernel) -----------------
+  const int hrow = wave * 32 + r;
+  int w1off[KS], xoff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    w1off[ks] = (hrow >> 6) * TB + tile_off<2 * D>(hrow & 63, 16 * ks + 8 * g);
+    xoff[ks] = tile_off<2 * D>(r, 16 * ks + 8 * g);
+  }
+  int uwoff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) uwoff[i] = r * UROW + (((wave * 4 + i) ^ swz<256>(r)) << 4) + 8 * g;
+  int uroff[KS2];
+#pragma unroll
+  for (int ks = 0; ks < KS2; ++ks) uroff[ks] = r * UROW + (((2 * ks + g) ^ swz<256>(r)) << 4);
+
+  float db2acc = 0.f, dzacc = 0.f;
+  const bool squared = (wave * 32 >= DP / 2);
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  for (int it = 0; it < n_tiles; ++it) {
+    const int valid = it < n_full ? 64 : rem;
+    const int soff = __builtin_amdgcn_readfirstlane(it * TB);
+    tile_load_asm<2 * D, TB, NW>(Xr, soff, lds_address(Xs), wave, lane, valid);
+    tile_load_asm<2 * D, TB, NW>(Vr, soff, lds_address(Vs), wave, lane, valid);
+    // weights of zv for this lane's accumulator rows (tokens 32 tb + 8 i + 4 g + j)
+    float tw[2][16];
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        int t = 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
+        if (t >= valid) t = valid - 1;
+        tw[tb][e] = Tw ? Tw[it * 64 + t] : 1.0f;
+      }
+    wait_loads_and_barrier<0>();   // tiles (and, on the first pass, W1) have landed
+
+    // ---- first half ----------------------------------------------------------
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      f32x16 u;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) u[e] = g ? b1hi[e] : b1lo[e];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 wf = *reinterpret_cast<const bf16x8*>(W1s + w1off[ks]);
+        bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + xoff[ks] + tb * (32 * 2 * D));
+        u = mfma(wf, xf, u);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        u32x2 pk;
+        pk[0] = pack_bf16(fmaxf(u[4 * i], 0.f), fmaxf(u[4 * i + 1], 0.f));
+        pk[1] = pack_bf16(fmaxf(u[4 * i + 2], 0.f), fmaxf(u[4 * i + 3], 0.f));
+        *reinterpret_cast<u32x2*>(Us + uwoff[i] + tb * (32 * UROW)) = pk;
+      }
+    }
+    lds_barrier();   // U complete
+
+    // U tile -> HBM, token-major, 16 bytes per store
+    {
+      constexpr int CPRU = UROW / 16;
+      constexpr int PER = 64 * CPRU / NT;
+#pragma unroll
+      for (int n = 0; n < PER; ++n) {
+        const int idx = tid + n * NT;
+        const int row = idx / CPRU, c = idx % CPRU;
+        if (row < valid) {
+          const u32x4 val = *reinterpret_cast<const u32x4*>(Us + row * UROW + ((c ^ swz<256>(row)) << 4));
+          *reinterpret_cast<u32x4*>(Ug + ((int64_t)it * 64 + row) * UROW + c * 16) = val;
+        }
+      }
+    }
+
+    // ---- second half ---------------------------------------------------------
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      f32x16 ps = zero, dphi = zero;
+#pragma unroll
+      for (int ks = 0; ks < KS2; ++ks) {
+        bf16x8 uf = *reinterpret_cast<const bf16x8*>(Us + uroff[ks] + tb * (32 * UROW));
+        ps = mfma(uf, w2f[ks], ps);
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vs + xoff[ks] + tb * (32 * 2 * D));
+        dphi = mfma(vf, mf[ks], dphi);
+      }
+      float pdb = 0.f, pdz = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int t = 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
+        const float psi = fmaxf(ps[e] + b2v, 0.f);
+        float dp = dphi[e] + tw[tb][e] * zvv;          // dL/dPhi
+        float ph = psi;
+        if (squared) {
+          dp = 2.f * psi * dp;                          // Phi = psi^2
+          ph = psi * psi;
+        } else if (!(psi > 0.f)) {
+          dp = 0.f;                                     // Phi = psi = relu(.)
+        }
+        if (t < valid) {
+          pdb += dp;
+          pdz += tw[tb][e] * ph;
+          Pg[((int64_t)it * 64 + t) * DP + unit] = (bf16_t)(pack_bf16(dp, 0.f) & 0xffffu);
+        }
+      }
+      db2acc += pdb;
+      dzacc += pdz;
+    }
+    lds_barrier();   // every wave is done with the tiles and U before the next loads land
+  }
+  if (n_tiles == 0) wait_loads_and_barrier<0>();   // W1 loads of an empty piece
+
+  const float db2 = half_swap_sum(db2acc);
+  const float dz = half_swap_sum(dzacc);
+  if (g == 0) {
+    a.db2_part[(int64_t)item * DP + unit] = db2;
+    if (a.dz_part) a.dz_part[(int64_t)item * DP + unit] = dz;
+  }
+}
+
+hipError_t launch_act_grad(const ActGradArgs& a, int d, int grid, hipStream_t stream) {
+  if (d == 128) hipLaunchKernelGGL((act_grad_kernel<128, 8>), dim3(grid), dim3(512), 0, stream, a);
+  else hipLaunchKernelGGL((act_grad_kernel<64, 4>), dim3(grid), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// token range of piece sp of nsplit: whole tiles of 64 from `lo`, the last tile ragged
+struct Piece {
+  int64_t tok0;
+  int n_tiles;    // tiles of this piece
+  int last_rows;  // valid rows of its last tile (64 unless it is the range's last tile)
+};
+__device__ __forceinline__ Piece piece_of(int64_t lo, int64_t hi, int sp, int nsplit) {
+  const int64_t nt = (hi - lo + 63) / 64;
+  const int64_t t0 = nt * sp / nsplit, t1 = nt * (sp + 1) / nsplit;
+  Piece p;
+  p.tok0 = lo + 64 * t0;
+  p.n_tiles = (int)(t1 - t0);
+  p.last_rows = 64;
+  if (t1 == nt && nt > 0) p.last_rows = (int)((hi - lo) - 64 * (nt - 1));
+  return p;
+}
+
+// ------------------------------------------------------------------------------------
+// dW2 partial: part[f][hid] = sum_tok dpsi[tok][f] U[tok][hid].  Both operands are token-major
+// tiles in LDS read with transposing loads (tokens become the contraction index).  Each
+// wave owns 64 rows f and half of the columns.
+// ------------------------------------------------------------------------------------
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW)
+tn_gemm_kernel(TnGemmArgs a) {
+  constexpr int W = 2 * D;          // columns of X and of Y
+  constexpr int ROWB = 2 * W;       // bytes per token row
+  constexpr int TBY = 64 * ROWB;    // tile bytes
+  constexpr int NT = 64 * NW;
+  constexpr int HB = W / 64;        // 32-column blocks per wave (half of the columns)
+  static_assert(W / 64 == NW / 2, "waves form a (W/64) x 2 grid");
+
+  __shared__ __attribute__((aligned(1024))) char Xs[TBY];
+  __shared__ __attribute__((aligned(1024))) char Ys[TBY];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, r = lane & 31, i16 = lane & 15;
+  const int wf = wave >> 1, wh = wave & 1;
+
+  const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);
+  if (item >= a.n_items) return;
+  const int sp = item % a.nsplit;
+  const int bh = item / a.nsplit;
+  const Piece pc = piece_of(a.lo, a.hi, sp, a.nsplit);
+  const int64_t row0 = (int64_t)bh * a.N + pc.tok0;
+  const u32x4 Xr = make_rsrc_words(a.X + row0 * W), Yr = make_rsrc_words(a.Y + row0 * W);
+
+  int xlo[2], xhi[2], ylo[HB], yhi[HB];
+#pragma unroll
+  for (int fb = 0; fb < 2; ++fb) {
+    const int col = 64 * wf + 32 * fb + 16 * (r >> 4) + 4 * (i16 & 3);
+    xlo[fb] = tile_off<ROWB>(4 * g + (i16 >> 2), col);
+    xhi[fb] = tile_off<ROWB>(8 + 4 * g + (i16 >> 2), col);
+  }
+#pragma unroll
+  for (int hb = 0; hb < HB; ++hb) {
+    const int col = (W / 2) * wh + 32 * hb + 16 * (r >> 4) + 4 * (i16 & 3);
+    ylo[hb] = tile_off<ROWB>(4 * g + (i16 >> 2), col);
+    yhi[hb] = tile_off<ROWB>(8 + 4 * g + (i16 >> 2), col);
+  }
+
+  f32x16 acc[2][HB];
+#pragma unroll
+  for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[fb][hb][e] = 0.f;
+
+  for (int it = 0; it < pc.n_tiles; ++it) {
+    const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
+    const int soff = __builtin_amdgcn_readfirstlane(it * TBY);
+    tile_load_asm<ROWB, TBY, NW>(Xr, soff, lds_address(Xs), wave, lane, valid);
+    tile_load_asm<ROWB, TBY, NW>(Yr, soff, lds_address(Ys), wave, lane, valid);
+    wait_loads_and_barrier<0>();
+    if (valid < 64) {  // rows past the range hold copies of the last row: clear them in X
+      const u32x4 z4 = {0u, 0u, 0u, 0u};
+      for (int o = valid * ROWB + tid * 16; o < TBY; o += NT * 16) *reinterpret_cast<u32x4*>(Xs + o) = z4;
+      lds_barrier();
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int so = s * 16 * ROWB;
+      bf16x8 af[2], bfr[HB];
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+        af[fb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Xs + xlo[fb] + so)),
+                         lds_read_tr(reinterpret_cast<const bf16_t*>(Xs + xhi[fb] + so)));
+#pragma unroll
+      for (int hb = 0; hb < HB; ++hb)
+        bfr[hb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Ys + ylo[hb] + so)),
+                          lds_read_tr(reinterpret_cast<const bf16_t*>(Ys + yhi[hb] + so)));
+#pragma unroll
+      for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+        for (int hb = 0; hb < HB; ++hb) acc[fb][hb] = mfma(af[fb], bfr[hb], acc[fb][hb]);
+    }
+    lds_barrier();
+  }
+
+  float* P = a.part + (int64_t)item * W * W;
+#pragma unroll
+  for (int fb = 0; fb < 2; ++fb)
+#pragma unroll
+    for (int hb = 0; hb < HB; ++hb)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int f = 64 * wf + 32 * fb + 8 * (e >> 2) + 4 * g + (e & 3);
+        P[f * W + (W / 2) * wh + 32 * hb + r] = acc[fb][hb][e];
+      }
+}
+
+hipError_t launch_tn_gemm(const TnGemmArgs& a, int d, int grid, hipStream_t stream) {
+  if (d == 128) hipLaunchKernelGGL((tn_gemm_kernel<128, 8>), dim3(grid), dim3(512), 0, stream, a);
+  else hipLaunchKernelGGL((tn_gemm_kernel<64, 4>), dim3(grid), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// First-layer gradients.  Per tile: dU slice = dpsi W2[:, slice] (tokens in accumulator rows,
+// the wave's 32 hidden units in lanes, W2^T rows resident as B operands), zero where U = 0;
+// then x^T dU into the wave's [d][32] slice of dW1^T, exactly as the chunk-state kernel
+// accumulates V^T phi.
+// ------------------------------------------------------------------------------------
+template <int D, int NW>
+__global__ void __launch_bounds__(64 * NW)
+hid_grad_kernel(HidGradArgs a) {
+  constexpr int HID = 2 * D, DP = 2 * D;
+  constexpr int KS2 = DP / 16;      // k-steps across the features
+  constexpr int DB = D / 32;
+  constexpr int TB = 64 * 2 * D;    // x tile
+  constexpr int UROW = HID * 2;     // bytes of a dpsi or U row
+  constexpr int TBU = 64 * UROW;
+  static_assert(HID / NW == 32, "each wave owns 32 hidden units");
+
+  __shared__ __attribute__((aligned(1024))) char Ps[TBU];
+  __shared__ __attribute__((aligned(1024))) char Um[TBU];
+  __shared__ __attribute__((aligned(1024))) char Xs[TB];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int g = lane >> 5, r = lane & 31, i16 = lane & 15;
+
+  const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);
+  if (item >= a.n_items) return;
+  const int sp = item % a.nsplit;
+  const int bh = item / a.nsplit;
+  const int h = bh % a.H;
+  const Piece pc = piece_of(a.lo, a.hi, sp, a.nsplit);
+  const int64_t row0 = (int64_t)bh * a.N + pc.tok0;
+  const u32x4 Pr = make_rsrc_words(a.dpsi + row0 * DP), Ur = make_rsrc_words(a.U + row0 * HID),
+              Xr = make_rsrc_words(a.x + row0 * D);
+
+  const int unit = wave * 32 + r;   // this lane's hidden unit
+  bf16x8 w2tf[KS2];                 // B operands: column = hidden unit, k = feature
+  {
+    const bf16_t* p = a.w2t + ((int64_t)h * HID + unit) * DP + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS2; ++ks) w2tf[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
+  int proff[KS2];
+#pragma unroll
+  for (int ks = 0; ks < KS2; ++ks) proff[ks] = r * UROW + (((2 * ks + g) ^ swz<256>(r)) << 4);
+  int voff_lo[DB], voff_hi[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    const int col = 32 * db + 16 * (r >> 4) + 4 * (i16 & 3);
+    voff_lo[db] = tile_off<2 * D>(4 * g + (i16 >> 2), col);
+    voff_hi[db] = tile_off<2 * D>(8 + 4 * g + (i16 >> 2), col);
+  }
+
+  f32x16 acc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[db][e] = 0.f;
+  float dbacc = 0.f;
+  const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  for (int it = 0; it < pc.n_tiles; ++it) {
+    const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
+    tile_load_asm<UROW, TBU, NW>(Pr, __builtin_amdgcn_readfirstlane(it * TBU), lds_address(Ps), wave, lane, valid);
+    tile_load_asm<UROW, TBU, NW>(Ur, __builtin_amdgcn_readfirstlane(it * TBU), lds_address(Um), wave, lane, valid);
+    tile_load_asm<2 * D, TB, NW>(Xr, __builtin_amdgcn_readfirstlane(it * TB), lds_address(Xs), wave, lane, valid);
+    wait_loads_and_barrier<0>();
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      f32x16 du = zero;
+#pragma unroll
+      for (int ks = 0; ks < KS2; ++ks) {
+        bf16x8 pf = *reinterpret_cast<const bf16x8*>(Ps + proff[ks] + tb * (32 * UROW));
+        du = mfma(pf, w2tf[ks], du);
+      }
+      float part = 0.f;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int t = 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
+        // U[t][unit] from the token-major tile (chunk = unit / 8, permuted by the row)
+        const int sw = ((e & 3) << 2) | ((2 * (e >> 2) + g) & 3);   // swz<256>(t)
+        const uint16_t ub = *reinterpret_cast<const uint16_t*>(
+            Um + t * UROW + ((((unit >> 3) ^ sw)) << 4) + (unit & 7) * 2);
+        float x = du[e];
+        if ((ub & 0x7fffu) == 0 || t >= valid) x = 0.f;
+        x = bf16_round(x);
+        du[e] = x;
+        part += x;
+      }
+      dbacc += part;
+#pragma unroll
+      for (int s = 0; s < 2; ++s) {
+        bf16x8 fb = acc_to_operand(du, s);
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const int so = (2 * tb + s) * (16 * 2 * D);
+          i16x4 vlo = lds_read_tr(reinterpret_cast<const bf16_t*>(Xs + voff_lo[db] + so));
+          i16x4 vhi = lds_read_tr(reinterpret_cast<const bf16_t*>(Xs + voff_hi[db] + so));
+          acc[db] = mfma(join_tr(vlo, vhi), fb, acc[db]);
+        }
+      }
+    }
+    lds_barrier();
+  }
+
+  float* P = a.part + (int64_t)item * (D * HID + HID);
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int row = 32 * db + 8 * (e >> 2) + 4 * g + (e & 3);
+      P[row * HID + unit] = acc[db][e];
+    }
+  const float tot = half_swap_sum(dbacc);
+  if (g == 0) P[D * HID + unit] = tot;
+}
+
+hipError_t launch_hid_grad(const HidGradArgs& a, int d, int grid, hipStream_t stream) {
+  if (d == 128) hipLaunchKernelGGL((hid_grad_kernel<128, 8>), dim3(grid), dim3(512), 0, stream, a);
+  else hipLaunchKernelGGL((hid_grad_kernel<64, 4>), dim3(grid), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------
+// Sum of the per-workgroup partials over batch and pieces, in a fixed order.
+// ------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+reduce_kernel(ReduceArgs a) {
+  const int h = blockIdx.y;
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int n = a.R * a.C;
+  if (i >= n) return;
+  float acc = 0.f;
+  for (int b = 0; b < a.B; ++b) {
+    const float* p = a.part + ((int64_t)(b * a.H + h) * a.per_bh) * a.part_stride + a.part_off + i;
+    for (int s = 0; s < a.per_bh; ++s) acc += p[(int64_t)s * a.part_stride];
+  }
+  int o = i;
+  if (a.transpose) o = (i % a.C) * a.R + i / a.C;
+  a.out[(int64_t)h * n + o] = acc;
+}
+
+hipError_t launch_reduce(const ReduceArgs& a, hipStream_t stream) {
+  dim3 grid((a.R * a.C + 255) / 256, a.H);
+  hipLaunchKernelGGL(reduce_kernel, grid, dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+__global__ void __launch_bounds__(256)
+fill_zero_kernel(float* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0.f;
+}
+
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+}  // namespace rehyat

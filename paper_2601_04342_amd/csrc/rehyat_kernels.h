@@ -30,6 +30,8 @@ struct StateArgs {
   int64_t kv_bh_stride; // elements between the k (and v) rows of consecutive (b, h)
   int step_n;           // > 0: one segment, rows [0, step_n) of k / v (streaming step); the
                         // frame geometry above is then unused
+  int query_segments;   // 1: segment s is the query range [q_lo, q_hi) of chunk chunk0 + s
+                        // (the sums of phi_q(q) u^T behind the gradient of the chunk state)
 };
 
 // ---- prefix kernel: states S_t, z_t of the window's chunks ---------------------
@@ -105,6 +107,109 @@ struct StateInArgs {
   float* carry;        // [BH, d*dprime + dprime]
   int BH, d, dprime;
 };
+
+// =================================================================================
+// Gradient of the output with respect to the feature-map parameters: one step of the
+// attention distillation of section 3.4 (Eq. 19) trains only phi_q and phi_k.
+// With G = dL/dy_hat, den_i = n^S_i + n^L_i, u_i = G_i / den_i, w_i = -(G_i . y_i) / den_i:
+//   dL/dPhi_q,i = S_t u_i + w_i z_t                 (queries of chunk t)
+//   dL/dS_t = sum_i Phi_q,i u_i^T ,  dL/dz_t = sum_i w_i Phi_q,i
+//   dL/dPhi_k,j = R_tau v_j + r_tau ,  R_tau = sum_{t > tau} dL/dS_t ,  r_tau likewise,
+// for keys j of segment tau = [s_lo(tau), s_lo(tau+1)) (Eq. 13: they belong to the linear
+// set of every later chunk), followed by the backward pass of the two-layer map.
+// =================================================================================
+
+// u = bf16(G / den), w = -(G . y) / den per token
+struct PrepArgs {
+  const bf16_t* g;    // [tokens, d] upstream gradient
+  const bf16_t* y;    // [tokens, d] forward output
+  const float* nS;    // [tokens]
+  const float* nL;    // [tokens]
+  bf16_t* u;          // [tokens, d]
+  float* tokw;        // [tokens]
+  int64_t tokens;
+  int d;
+};
+
+// R_tau, r_tau: sums over the later chunks of the chunk-state gradients
+struct SuffixArgs {
+  const float* s_part;  // [BH, s_slots, elems]: segment s, piece p at slot s*s_nsplit + p; S^T part used
+  const float* z_part;  // [(bh*n_seg + s)*z_nsplit + p][dp]
+  bf16_t* Rt;           // [BH, slots, d, dp]  (transposed, as the forward states)
+  float* r;             // [BH, slots, dp]
+  int BH, n_seg, s_nsplit, s_slots, z_nsplit, slots;
+  int elems, s_elems, dp;
+};
+
+// bf16 matrices [n][R][C] -> [n][C][R]
+struct TransposeArgs {
+  const bf16_t* in;
+  bf16_t* out;
+  int n, R, C;
+};
+
+// Activation gradients of one side (queries or keys): recomputes U = relu(W1 x + b1) and
+// psi = relu(W2 U + b2), forms dPhi = M vec + tokw * zv for the token's segment, and writes
+// U and dpsi = dPhi * dphi/dpsi token-major for the weight-gradient kernels.
+struct ActGradArgs {
+  const bf16_t* x;      // [BH, N, d]  q or k
+  const bf16_t* vec;    // [BH, N, d]  u (query side) or v (key side)
+  const float* tokw;    // [BH, N] per-token weight of zv, or null for 1
+  const bf16_t* w1;
+  const float* b1;
+  const bf16_t* w2;
+  const float* b2;
+  const bf16_t* M;      // [BH, slots, dp, d]  S_t (query side) or R_tau (key side)
+  const float* zv;      // [BH, slots, dp]     z_t or r_tau
+  bf16_t* U;            // [BH, N, hidden]
+  bf16_t* dpsi;         // [BH, N, dp]
+  float* db2_part;      // [n_items, dp]  sum over the item's tokens of dpsi
+  float* dz_part;       // [n_items, dp]  sum of tokw * phi (query side), or null
+  int H, T, HW, chunk, overlap;
+  int query_side;       // 1: segment s = queries of chunk s+1, slot s+1; 0: key segment s, slot s
+  int n_seg, nsplit, slots, n_items, items_per_xcd;
+};
+
+// dW2 partial sums: part[f][hid] = sum over a token range of dpsi[tok][f] * U[tok][hid]
+struct TnGemmArgs {
+  const bf16_t* X;      // [BH, N, 2d]  dpsi
+  const bf16_t* Y;      // [BH, N, 2d]  U
+  float* part;          // [BH * nsplit, 2d, 2d]
+  int64_t N, lo, hi;    // token range [lo, hi) of every (b, h)
+  int nsplit, n_items, items_per_xcd;
+};
+
+// First-layer gradients: dU = (dpsi W2) * [U > 0];  part = x^T dU ([d][hidden]), then the
+// column sums of dU ([hidden])
+struct HidGradArgs {
+  const bf16_t* dpsi;   // [BH, N, dp]
+  const bf16_t* U;      // [BH, N, hidden]
+  const bf16_t* x;      // [BH, N, d]
+  const bf16_t* w2t;    // [H, hidden, dp]  W2 transposed
+  float* part;          // [BH * nsplit, d*hidden + hidden]
+  int H;
+  int64_t N, lo, hi;
+  int nsplit, n_items, items_per_xcd;
+};
+
+// out[h][..] = sum over b and the per_bh partials of (b, h) of an [R][C] block found at
+// part_off inside each partial; transposed on the way out if `transpose`
+struct ReduceArgs {
+  const float* part;
+  float* out;           // [H, R*C]
+  int B, H, per_bh;
+  int64_t part_stride, part_off;
+  int R, C, transpose;
+};
+
+hipError_t launch_prep(const PrepArgs& a, hipStream_t stream);
+hipError_t launch_suffix(const SuffixArgs& a, hipStream_t stream);
+hipError_t launch_transpose(const TransposeArgs& a, hipStream_t stream);
+hipError_t launch_act_grad(const ActGradArgs& a, int d, int grid, hipStream_t stream);
+hipError_t launch_tn_gemm(const TnGemmArgs& a, int d, int grid, hipStream_t stream);
+hipError_t launch_hid_grad(const HidGradArgs& a, int d, int grid, hipStream_t stream);
+hipError_t launch_reduce(const ReduceArgs& a, hipStream_t stream);
+hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t stream);
 
 hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream);
 hipError_t launch_prefix(const PrefixArgs& a, hipStream_t stream);

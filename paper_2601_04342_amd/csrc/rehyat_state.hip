@@ -67,9 +67,15 @@ state_kernel(StateArgs a) {
   if (a.step_n <= 0) {
     const int tt = a.chunk0 + seg;
     const int nchunks = num_chunks(a.T, a.chunk);
-    seg_lo = chunk_range(a.T, a.HW, a.chunk, a.overlap, tt).s_lo;
-    seg_hi = (tt + 1 < nchunks) ? chunk_range(a.T, a.HW, a.chunk, a.overlap, tt + 1).s_lo
-                                : (int64_t)a.T * a.HW;
+    const ChunkRange cr = chunk_range(a.T, a.HW, a.chunk, a.overlap, tt);
+    if (a.query_segments) {   // the queries of chunk tt (gradient of the chunk state)
+      seg_lo = cr.q_lo;
+      seg_hi = cr.q_hi;
+    } else {
+      seg_lo = cr.s_lo;
+      seg_hi = (tt + 1 < nchunks) ? chunk_range(a.T, a.HW, a.chunk, a.overlap, tt + 1).s_lo
+                                  : (int64_t)a.T * a.HW;
+    }
   }
   const int64_t len = seg_hi - seg_lo;
   const int64_t lo = seg_lo + (len * sp) / a.nsplit;

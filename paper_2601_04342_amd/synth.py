@@ -78,6 +78,12 @@ def make_qkv(B, H, N, d, seed=0, rms_norm=True):
     return tuple(out)
 
 
+def make_grad_out(B, H, N, d, seed=2):
+    """A stand-in for dL/dy_hat: N(0,1) draws rounded to bf16 values, fp32 CPU [B, H, N, d]."""
+    g = torch.Generator(device="cpu").manual_seed(seed)
+    return round_bf16(torch.randn(B, H, N, d, generator=g, dtype=torch.float32))
+
+
 PHI_NAMES = ("w1_q", "b1_q", "w2_q", "b2_q", "w1_k", "b1_k", "w2_k", "b2_k")
 
 

@@ -1,0 +1,146 @@
+"""GPU parity of the feature-map gradient (rehyat_phi_backward, Eq. 19) against the fp64
+gradient oracle, element by element, on the same seeded bf16-rounded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import grad as ograd
+from paper_2601_04342_amd import binding, synth
+from tests import parity
+
+pytestmark = pytest.mark.gpu
+
+# Bars on each of the eight gradient tensors, relative to the tensor's own scale.  Every entry
+# is a sum over tokens of signed products whose factors pass through bf16 on the GPU (MFMA
+# operands): u = G/den, Phi_q, the states S_t and R_tau, dpsi, dU, and y_hat inside w -- up to
+# six roundings of relative size <= 2^-8 (rms 2^-9 / sqrt 3 = 1.1e-3) along one path, fp32
+# accumulation.  The terms of a sum have random signs, so the relative error of the sum stays at
+# the level of one term's: about sqrt(6) * 1.1e-3 = 2.8e-3 in the Frobenius norm (4e-3 to 5e-3 when
+# the roundings are replayed in numpy on the first cases below); the bars leave a factor two
+# to four.  The hidden activations U are bf16 on both sides (hidden_round of the oracle), so
+# the ReLU gates of the second layer are decided on the same values.
+MAX_REL = 2e-2    # max |gpu - ref| <= MAX_REL * max |ref|
+FRO_REL = 1e-2    # ||gpu - ref||_F <= FRO_REL * ||ref||_F
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"[gpu-test] {request.node.nodeid}", flush=True)
+    yield
+    torch.cuda.synchronize()
+
+
+def check_grads(grads, ref, label):
+    worst = 0.0
+    for name in synth.PHI_NAMES:
+        g = grads[name].cpu().double().numpy()
+        r = ref[name]
+        assert np.isfinite(g).all(), (label, name)
+        scale = np.abs(r).max()
+        emax = np.abs(g - r).max()
+        efro = np.linalg.norm(g - r) / max(np.linalg.norm(r), 1e-300)
+        print(f"   {name}: max-abs err / max |ref| = {emax / max(scale, 1e-300):.2e}   "
+              f"relative Frobenius = {efro:.2e}   max |ref| = {scale:.3e}", flush=True)
+        if scale == 0.0:
+            assert emax == 0.0, (label, name)
+            continue
+        assert emax <= MAX_REL * scale, (label, name, emax, scale)
+        assert efro <= FRO_REL, (label, name, efro)
+        worst = max(worst, efro)
+    return worst
+
+
+def run_case(B, H, T, HW, d, chunk, overlap, gain, seed, l1=False):
+    N = T * HW
+    q, k, v = synth.make_qkv(B, H, N, d, seed=seed)
+    phi = synth.make_phi(H, d, seed=seed + 1, gain=gain)
+    if l1:
+        # G of the L1 loss of Eq. 19 against a random teacher: +-1/count, exact in bf16 for
+        # a power-of-two count; the sign pattern comes from a seeded draw, not from y_hat
+        G = torch.sign(synth.make_grad_out(B, H, N, d, seed=seed + 2)) / 65536.0
+    else:
+        G = synth.make_grad_out(B, H, N, d, seed=seed + 2)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    dG = G.to("cuda", torch.bfloat16).contiguous()
+    grads = {n: torch.full(t.shape, float("nan"), device="cuda", dtype=torch.float32)
+             for n, t in dphi.items()}
+    grads, y = binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, chunk, overlap=overlap,
+                                    out=parity.nan_like(dq), grads=grads)
+    torch.cuda.synchronize()
+    qn, kn, vn, pn = parity.oracle_inputs(q, k, v, phi)
+    ref, y_ref = ograd.phi_backward(qn, kn, vn, pn, G.double().numpy(), T, HW, chunk, overlap,
+                                        hidden_round="bf16")
+    label = f"B{B} H{H} T{T} HW{HW} d{d} chunk{chunk} ov{overlap} gain{gain}"
+    yerr = np.abs(y.float().cpu().double().numpy() - y_ref)
+    assert np.isfinite(yerr).all(), label
+    assert yerr.max() <= parity.OUT_MAX_ABS and yerr.mean() <= parity.OUT_MEAN_ABS, (label, yerr.max())
+    return check_grads(grads, ref, label)
+
+
+CASES = [
+    # B, H, T, HW, d, chunk, overlap, gain
+    (1, 2, 4, 64, 64, 1, 0, 8.0),
+    (2, 3, 5, 77, 128, 2, 0, 4.0),      # T % chunk != 0, ragged tiles, batch sum
+    (1, 2, 5, 77, 128, 2, 1, 4.0),      # overlapping windows: key segments lag the chunks
+    (1, 2, 7, 50, 64, 3, 2, 6.0),
+    (1, 2, 4, 30, 64, 1, 3, 6.0),       # overlap reaches the first frame: empty key segments
+    (1, 2, 6, 700, 128, 1, 0, 2.0),     # many tiles per segment
+    (1, 1, 4, 2000, 128, 1, 0, 2.0),    # few (b, h, segment): segments are split
+    (1, 2, 40, 20, 64, 1, 0, 3.0),      # many short chunks (segments shorter than a tile)
+    (1, 1, 2, 1, 128, 1, 0, 1.0),       # two tokens (small phi: with a dominant linear part the
+                                        # single query's gradient is a difference of nearly equal terms)
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_small_shapes_match_gradient_oracle(case):
+    run_case(*case, seed=sum(case[:7]))
+
+
+def test_l1_distillation_gradient():
+    run_case(1, 2, 5, 200, 128, 1, 0, 4.0, seed=5, l1=True)
+
+
+def test_one_chunk_gives_zero_gradients():
+    B, H, T, HW, d = 1, 2, 3, 100, 128
+    q, k, v = synth.make_qkv(B, H, T * HW, d, seed=3)
+    phi = synth.make_phi(H, d, seed=4, gain=4.0)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    dG = synth.make_grad_out(B, H, T * HW, d).to("cuda", torch.bfloat16)
+    grads = {n: torch.full(t.shape, float("nan"), device="cuda", dtype=torch.float32)
+             for n, t in dphi.items()}
+    grads, y = binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, T, grads=grads)
+    torch.cuda.synchronize()
+    for n in synth.PHI_NAMES:
+        assert (grads[n] == 0).all(), n
+    assert torch.equal(y, binding.forward(dq, dk, dv, dphi, T, HW, T))
+
+
+def test_backward_is_reproducible_and_leaves_inputs_alone():
+    B, H, T, HW, d = 1, 2, 5, 150, 128
+    q, k, v = synth.make_qkv(B, H, T * HW, d, seed=8)
+    phi = synth.make_phi(H, d, seed=9, gain=4.0)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    dG = synth.make_grad_out(B, H, T * HW, d).to("cuda", torch.bfloat16)
+    keep = [t.clone() for t in (dq, dk, dv, dG)]
+    g1, y1 = binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, 1)
+    g2, y2 = binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, 1)
+    torch.cuda.synchronize()
+    for n in synth.PHI_NAMES:
+        assert torch.equal(g1[n], g2[n]), n
+    assert torch.equal(y1, y2)
+    for a, b in zip(keep, (dq, dk, dv, dG)):
+        assert torch.equal(a, b)
+
+
+def test_workspace_too_small_is_refused():
+    B, H, T, HW, d = 1, 2, 4, 64, 64
+    q, k, v = synth.make_qkv(B, H, T * HW, d)
+    phi = synth.make_phi(H, d)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    dG = dq.clone()
+    need = binding.phi_backward_workspace_bytes(B, H, T, HW, d, 1)
+    ws = torch.empty(need - 256, device="cuda", dtype=torch.uint8)
+    with pytest.raises(binding.RehyatError) as e:
+        binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, 1, workspace=ws)
+    assert e.value.code == binding.E_WORKSPACE

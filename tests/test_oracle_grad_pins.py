@@ -116,3 +116,33 @@ def test_dead_feature_and_first_chunk_queries_get_no_gradient():
     g0, _ = grad.phi_backward(q, k, v, phi, G0, 2, 6, 1)
     for name in NAMES:
         assert np.abs(g0[name]).max() == 0.0
+
+
+def test_bf16_rounding_helper_and_hidden_round_option():
+    """round_to_bf16 against hand-worked bit patterns (nearest, ties to even), and the
+    hidden_round option: identical results when U is already representable in bf16."""
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -9, 1.0 + 3 * 2.0 ** -9,
+                  1.0 + 2.0 ** -7 + 2.0 ** -8, -2.5, 0.0, 1e-3])
+    got = grad.round_to_bf16(x)        # bf16 keeps 7 fraction bits: spacing 2^-7 in [1, 2)
+    assert got[0] == 1.0 and got[5] == -2.5 and got[6] == 0.0
+    assert got[1] == 1.0                      # exactly half way: ties to the even mantissa
+    assert got[2] == 1.0                      # below half way
+    assert got[3] == 1.0 + 2.0 ** -7          # above half way
+    assert got[4] == 1.0 + 2.0 ** -6          # half way again, the even neighbour is the upper one
+    assert abs(got[7] - 1e-3) <= 2.0 ** -8 * 1e-3
+    # a first layer whose outputs are small integers: rounding changes nothing
+    rng = np.random.default_rng(21)
+    B, H, T, HW, d, hidden, dprime = 1, 1, 3, 4, 4, 6, 4
+    q = rng.integers(-2, 3, (B, H, T * HW, d)).astype(float)
+    k = rng.integers(-2, 3, (B, H, T * HW, d)).astype(float)
+    v = rng.standard_normal((B, H, T * HW, d))
+    phi = {"w1_q": rng.integers(-1, 2, (H, hidden, d)).astype(float), "b1_q": np.zeros((H, hidden)),
+           "w2_q": rng.standard_normal((H, dprime, hidden)) * 0.3, "b2_q": rng.standard_normal((H, dprime)) * 0.1,
+           "w1_k": rng.integers(-1, 2, (H, hidden, d)).astype(float), "b1_k": np.zeros((H, hidden)),
+           "w2_k": rng.standard_normal((H, dprime, hidden)) * 0.3, "b2_k": rng.standard_normal((H, dprime)) * 0.1}
+    G = rng.standard_normal(q.shape)
+    g0, y0 = grad.phi_backward(q, k, v, phi, G, T, HW, 1)
+    g1, y1 = grad.phi_backward(q, k, v, phi, G, T, HW, 1, hidden_round="bf16")
+    assert np.array_equal(y0, y1)
+    for name in NAMES:
+        assert np.array_equal(g0[name], g1[name])

@@ -46,7 +46,8 @@ def test_host_layer_under_asan_ubsan(tmp_path):
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-Wno-unused-command-line-argument"]
     cmd += [os.path.join(CSRC, s) for s in ("rehyat_api.hip", "rehyat_state.hip",
-                                            "rehyat_prefix.hip", "rehyat_attn.hip")]
+                                            "rehyat_prefix.hip", "rehyat_attn.hip",
+                                            "rehyat_grad.hip")]
     cmd += [os.path.join(ROOT, "tests", "sanitize", "host_driver.cpp"), "-o", exe]
     subprocess.run(cmd, check=True, capture_output=True, text=True, timeout=900)
     r = _run(exe)
