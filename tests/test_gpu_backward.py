@@ -144,3 +144,40 @@ def test_workspace_too_small_is_refused():
     with pytest.raises(binding.RehyatError) as e:
         binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, 1, workspace=ws)
     assert e.value.code == binding.E_WORKSPACE
+
+
+def full_size_case(name, overlap, heads, seed_g=2):
+    """A benchmark-size workload in the launch configuration bench.py --mode backward times;
+    the oracle evaluates the first `heads` heads completely (gradients are per head, B = 1)."""
+    w = synth.WORKLOADS[name]
+    q, k, v, phi = synth.make_workload(w)
+    G = synth.make_grad_out(w.B, w.H, w.N, w.d, seed=seed_g)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    dG = G.to("cuda", torch.bfloat16).contiguous()
+    grads = {n: torch.full(t.shape, float("nan"), device="cuda", dtype=torch.float32)
+             for n, t in dphi.items()}
+    grads, y = binding.phi_backward(dq, dk, dv, dphi, dG, w.T, w.HW, w.chunk, overlap=overlap,
+                                    out=parity.nan_like(dq), grads=grads)
+    torch.cuda.synchronize()
+    for n in synth.PHI_NAMES:
+        assert torch.isfinite(grads[n]).all(), n
+    assert torch.isfinite(y.float()).all()
+    hs = slice(0, heads)
+    qn, kn, vn, pn = parity.oracle_inputs(q, k, v, phi, heads=hs)
+    ref, y_ref = ograd.phi_backward(qn, kn, vn, pn, G[:, hs].double().numpy(), w.T, w.HW, w.chunk,
+                                    overlap, hidden_round="bf16")
+    yerr = np.abs(y[:, hs].float().cpu().double().numpy() - y_ref)
+    assert yerr.max() <= parity.OUT_MAX_ABS and yerr.mean() <= parity.OUT_MEAN_ABS, yerr.max()
+    check_grads({n: g[hs] for n, g in grads.items()}, ref, f"{name} ov{overlap}")
+
+
+def test_wan480p_every_entry_of_every_gradient():
+    """The 480p layer shape (B=1, H=12, d=128, 32,760 tokens, chunk 1): all 2.37 M gradient
+    entries against the oracle."""
+    full_size_case("wan480p", 0, 12)
+
+
+def test_p320_chunk3_overlap1_gradients():
+    """320x480 shape with the paper's preferred T_c = 3, T_o = 1 (section 4.1): key segments
+    lag the chunks by one frame."""
+    full_size_case("p320_t21_c3", 1, 4)
