@@ -428,7 +428,7 @@ struct BwdPlan {
   int nc, n_seg;     // chunks; segments (= chunks that read a state)
   int nsplit;        // pieces per segment (state and activation-gradient kernels)
   int nsplit_g;      // pieces per (b, h) of the weight-gradient kernels
-  size_t yhat, nS, nL, u, tokw, Sn, Rt, Rn, rz, w2t_q, w2t_k, U, dpsi, p_w2, p_w1, p_b2, p_dz, total;
+  size_t yhat, nS, nL, u, tokw, Sn, Rt, Rn, rz, w2t_q, w2t_k, dpsi, p_w2, p_w1, p_b2, p_dz, total;
 };
 
 BwdPlan bwd_plan(int B, int H, int T, int HW, int d, int chunk) {
@@ -463,7 +463,6 @@ BwdPlan bwd_plan(int B, int H, int T, int HW, int d, int chunk) {
   P.rz = take(BH * P.nc * (size_t)dp * sizeof(float));
   P.w2t_q = take((size_t)H * hid * dp * sizeof(bf16_t));
   P.w2t_k = take((size_t)H * hid * dp * sizeof(bf16_t));
-  P.U = take(BH * N * hid * sizeof(bf16_t));
   P.dpsi = take(BH * N * dp * sizeof(bf16_t));
   P.p_w2 = take(BH * ns * (size_t)dp * hid * sizeof(float));
   P.p_w1 = take(BH * ns * ((size_t)d * hid + hid) * sizeof(float));
@@ -497,7 +496,6 @@ int backward_side(char* ws, const BwdPlan& P, hipStream_t st, const void* x, con
   g.b2 = (const float*)sp.b2;
   g.M = M;
   g.zv = zv;
-  g.U = (bf16_t*)(ws + P.U);
   g.dpsi = (bf16_t*)(ws + P.dpsi);
   g.db2_part = (float*)(ws + P.p_b2);
   g.dz_part = dz_part;
@@ -515,25 +513,14 @@ int backward_side(char* ws, const BwdPlan& P, hipStream_t st, const void* x, con
   hipError_t e = launch_act_grad(g, d, g.items_per_xcd * 8, st);
   if (e != hipSuccess) return hip_fail(e, "activation-gradient kernel launch");
 
-  ReduceArgs r;
-  r.B = B;
-  r.H = H;
-  r.part = (const float*)(ws + P.p_b2);
-  r.out = sp.g_b2;
-  r.per_bh = P.n_seg * P.nsplit;
-  r.part_stride = dp;
-  r.part_off = 0;
-  r.R = 1;
-  r.C = dp;
-  r.transpose = 0;
-  e = launch_reduce(r, st);
-  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
-
   const int n_items = BH * P.nsplit_g;
   TnGemmArgs t;
-  t.X = (const bf16_t*)(ws + P.dpsi);
-  t.Y = (const bf16_t*)(ws + P.U);
+  t.dpsi = (const bf16_t*)(ws + P.dpsi);
+  t.x = (const bf16_t*)x;
+  t.w1 = (const bf16_t*)sp.w1;
+  t.b1 = (const float*)sp.b1;
   t.part = (float*)(ws + P.p_w2);
+  t.H = H;
   t.N = (int64_t)T * HW;
   t.lo = lo;
   t.hi = hi;
@@ -542,21 +529,12 @@ int backward_side(char* ws, const BwdPlan& P, hipStream_t st, const void* x, con
   t.items_per_xcd = (n_items + 7) / 8;
   e = launch_tn_gemm(t, d, t.items_per_xcd * 8, st);
   if (e != hipSuccess) return hip_fail(e, "second-layer gradient kernel launch");
-  r.part = (const float*)(ws + P.p_w2);
-  r.out = sp.g_w2;
-  r.per_bh = P.nsplit_g;
-  r.part_stride = (int64_t)dp * hid;
-  r.part_off = 0;
-  r.R = dp;
-  r.C = hid;
-  r.transpose = 0;
-  e = launch_reduce(r, st);
-  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
 
   HidGradArgs hg;
   hg.dpsi = (const bf16_t*)(ws + P.dpsi);
-  hg.U = (const bf16_t*)(ws + P.U);
   hg.x = (const bf16_t*)x;
+  hg.w1 = (const bf16_t*)sp.w1;
+  hg.b1 = (const float*)sp.b1;
   hg.w2t = w2t;
   hg.part = (float*)(ws + P.p_w1);
   hg.H = H;
@@ -568,22 +546,46 @@ int backward_side(char* ws, const BwdPlan& P, hipStream_t st, const void* x, con
   hg.items_per_xcd = (n_items + 7) / 8;
   e = launch_hid_grad(hg, d, hg.items_per_xcd * 8, st);
   if (e != hipSuccess) return hip_fail(e, "first-layer gradient kernel launch");
-  r.part = (const float*)(ws + P.p_w1);
-  r.per_bh = P.nsplit_g;
-  r.part_stride = (int64_t)d * hid + hid;
-  r.out = sp.g_w1;   // partial is dW1^T [d][hidden]
-  r.part_off = 0;
-  r.R = d;
-  r.C = hid;
-  r.transpose = 1;
-  e = launch_reduce(r, st);
-  if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
-  r.out = sp.g_b1;
-  r.part_off = (int64_t)d * hid;
-  r.R = 1;
-  r.C = hid;
-  r.transpose = 0;
-  e = launch_reduce(r, st);
+
+  // the four gradient tensors of this side from their partial sums, one launch
+  ReduceJobs jobs;
+  jobs.n = 4;
+  for (int j = 0; j < 4; ++j) {
+    jobs.job[j].B = B;
+    jobs.job[j].H = H;
+    jobs.job[j].part_off = 0;
+    jobs.job[j].transpose = 0;
+  }
+  ReduceArgs& rw2 = jobs.job[0];
+  rw2.part = (const float*)(ws + P.p_w2);
+  rw2.out = sp.g_w2;
+  rw2.per_bh = P.nsplit_g;
+  rw2.part_stride = (int64_t)dp * hid;
+  rw2.R = dp;
+  rw2.C = hid;
+  ReduceArgs& rw1 = jobs.job[1];   // partial is dW1^T [d][hidden]
+  rw1.part = (const float*)(ws + P.p_w1);
+  rw1.out = sp.g_w1;
+  rw1.per_bh = P.nsplit_g;
+  rw1.part_stride = (int64_t)d * hid + hid;
+  rw1.R = d;
+  rw1.C = hid;
+  rw1.transpose = 1;
+  ReduceArgs& rb1 = jobs.job[2];
+  rb1 = rw1;
+  rb1.out = sp.g_b1;
+  rb1.part_off = (int64_t)d * hid;
+  rb1.R = 1;
+  rb1.C = hid;
+  rb1.transpose = 0;
+  ReduceArgs& rb2 = jobs.job[3];
+  rb2.part = (const float*)(ws + P.p_b2);
+  rb2.out = sp.g_b2;
+  rb2.per_bh = P.n_seg * P.nsplit;
+  rb2.part_stride = dp;
+  rb2.R = 1;
+  rb2.C = dp;
+  e = launch_reduce(jobs, st);
   if (e != hipSuccess) return hip_fail(e, "reduce kernel launch");
   return REHYAT_OK;
 }

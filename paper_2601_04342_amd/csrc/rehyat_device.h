@@ -197,6 +197,12 @@ __device__ __forceinline__ void direct_load_16(u32x4 rsrc, int voff, int soff, u
                ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
                : "memory");
 }
+// Four bytes per lane: lane i writes bytes [4 i, 4 i + 4) of the 256-byte block at lds_addr.
+__device__ __forceinline__ void direct_load_4(u32x4 rsrc, int voff, int soff, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+               ::"s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff)
+               : "memory");
+}
 __device__ __forceinline__ uint32_t lds_address(const void* p) {
   return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p;
 }
@@ -218,6 +224,39 @@ __device__ __forceinline__ void tile_load_asm(u32x4 rsrc, int soff, uint32_t lds
     const int c = (lane % CPR) ^ swz<ROWBYTES>(R);
     if (R >= valid) R = valid - 1;
     direct_load_16(rsrc, R * ROWBYTES + c * 16, soff, lds_tile + blk * 1024);
+  }
+}
+
+// tile_load_asm with one per-lane offset for every block a wave moves when the tile is full
+// (valid == 64): block b of a wave differs from its first block by whole multiples of 16
+// rows, which the chunk permutation does not see, so the block part goes into the scalar
+// offset and the per-lane offset is loop-invariant (one register per tile shape instead of
+// one per load).  `voff_full` is that offset, from tile_voff_full; a ragged tile takes the
+// general path.
+template <int ROWBYTES, int NW>
+__device__ __forceinline__ int tile_voff_full(int wave, int lane) {
+  constexpr int CPR = ROWBYTES / 16;
+  constexpr int RPB = 1024 / ROWBYTES;
+  static_assert((NW * RPB) % 16 == 0, "blocks of a wave are whole multiples of 16 rows apart");
+  const int j = lane / CPR;
+  return j * ROWBYTES + (((lane % CPR) ^ swz<ROWBYTES>(wave * RPB + j)) << 4);
+}
+template <int ROWBYTES, int TILE_BYTES, int NW>
+__device__ __forceinline__ void tile_load_fast(u32x4 rsrc, int soff, uint32_t lds_tile, int wave, int lane,
+                                               int valid, int voff_full) {
+  constexpr int NBLK = TILE_BYTES / 1024;
+  static_assert(NBLK % NW == 0, "blocks of a tile are dealt evenly to the waves");
+  if (valid >= 64) {
+#pragma unroll
+    for (int n = 0; n < NBLK / NW; ++n) {
+      const int blk = wave + NW * n;
+      direct_load_16(rsrc, voff_full, soff + blk * 1024, lds_tile + blk * 1024);
+    }
+  } else {
+    // at most once per token range: keep its per-load offsets from being computed ahead of
+    // the loop and held in registers (the empty asm hides that they are loop-invariant)
+    asm volatile("" : "+s"(valid), "+v"(lane));
+    tile_load_asm<ROWBYTES, TILE_BYTES, NW>(rsrc, soff, lds_tile, wave, lane, valid);
   }
 }
 

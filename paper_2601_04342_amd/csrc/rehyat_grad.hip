@@ -13,11 +13,11 @@
 // Kernels, in launch order for one side (queries, then keys):
 //   prep_kernel       u, w per token (HBM-bound)
 //   state_kernel      (rehyat_state.hip, query segments) dL/dS_t partial sums
-//   act_grad_kernel   recomputes U and psi, forms dPhi and dpsi per token; writes U and dpsi
+//   act_grad_kernel   recomputes U and psi, forms dPhi and dpsi per token; writes dpsi
 //                     token-major, and the partial sums of db2 and dL/dz_t
 //   suffix_kernel     R_tau, r_tau from the partial sums
-//   tn_gemm_kernel    dW2 = dpsi^T U over tokens
-//   hid_grad_kernel   dU = (dpsi W2) [U > 0]; dW1 = dU^T x, db1 = sum dU
+//   tn_gemm_kernel    dW2 = dpsi^T U over tokens (U recomputed from x)
+//   hid_grad_kernel   dU = (dpsi W2) [U > 0]; dW1 = dU^T x, db1 = sum dU (sign of U recomputed)
 //   reduce_kernel     sums the per-workgroup partials over batch and pieces
 // The contraction kernels follow the chunk-state kernel's scheme: wave w owns 32 hidden
 // units or features, weights of its slice live in registers as MFMA B operands, tiles of 64
@@ -141,28 +141,42 @@ hipError_t launch_transpose(const TransposeArgs& a, hipStream_t stream) {
 }
 
 // ------------------------------------------------------------------------------------
-// Activation gradients.  Per tile of 64 tokens:
-//   first half   U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden]
-//                (as in the chunk-state kernel), and from there to HBM;
+// Activation gradients.  Wave w owns hidden units and features [32w, 32w + 32); its rows of
+// W1, W2 and of the segment's matrix M stay in registers as MFMA operands for the whole token
+// range.  Per tile of 64 tokens:
+//   first half   U^T slice = relu(W1[slice] X^T + b1[slice]) -> LDS as U[token][hidden];
 //   second half  psi slice = U W2[slice]^T + b2 and dPhi slice = Vec M[slice]^T, both with
 //                tokens in accumulator rows and the wave's 32 features in lanes;
-//                dpsi = dPhi + w zv, times 2 psi in the squared half, zero where psi = 0.
+//                dpsi = dPhi + w zv, times 2 psi in the squared half, zero where psi = 0;
+//                dpsi goes through a wave-private LDS patch so that it leaves in 16-byte stores.
+// The x and vec tiles (and the 64 token weights) of tile t+2 are requested when tile t is
+// finished, into the buffers tile t used; they are ordered against the reads by counted
+// waits.  Vector memory operations of a wave complete in the order issued, stores included,
+// so "at most n outstanding" after n younger stores means every older load has landed.
 // ------------------------------------------------------------------------------------
-template <int D, int NW>
+template <int D, int NW, bool TW>
 __global__ void __launch_bounds__(64 * NW)
 act_grad_kernel(ActGradArgs a) {
   constexpr int HID = 2 * D, DP = 2 * D;
   constexpr int KS = D / 16;
   constexpr int KS2 = HID / 16;
-  constexpr int NT = 64 * NW;
-  constexpr int TB = 64 * 2 * D;  // bytes of an x, vec or W1 tile
+  constexpr int TB = 64 * 2 * D;  // bytes of an x or vec tile
   constexpr int UROW = HID * 2;
+  constexpr int LPT = TB / (1024 * NW);
+  constexpr int LG = 2 * LPT + (TW ? 1 : 0);  // direct loads per wave per tile
+  constexpr int SROW = 80;        // bytes per token row of the dpsi patch: 32 features + padding
+  constexpr int NST = 4;          // dpsi stores per lane per full tile
+  // U[token][hidden] with 16 bytes of padding per row: consecutive rows start four banks apart,
+  // so fragment reads and writes are conflict-free without a chunk permutation and every
+  // k-step is an immediate offset from one per-lane address
+  constexpr int UPAD = UROW + 16;
   static_assert(DP / NW == 32, "each wave owns 32 features");
 
-  __shared__ __attribute__((aligned(1024))) char W1s[(HID / 64) * TB];
-  __shared__ __attribute__((aligned(1024))) char Xs[TB];
-  __shared__ __attribute__((aligned(1024))) char Vs[TB];
-  __shared__ __attribute__((aligned(1024))) char Us[64 * UROW];
+  __shared__ __attribute__((aligned(1024))) char XV[4 * TB];   // x tiles 0/1, then vec tiles 0/1
+  __shared__ __attribute__((aligned(1024))) char Us[64 * UPAD];
+  __shared__ __attribute__((aligned(1024))) char Stg[NW * 32 * SROW];
+  __shared__ __attribute__((aligned(256))) float Tws[2 * 64];
+  __shared__ __attribute__((aligned(256))) float B1s[HID];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -199,32 +213,25 @@ act_grad_kernel(ActGradArgs a) {
   const int n_tiles = n_full + (rem > 0 ? 1 : 0);
 
   const int64_t row0 = (int64_t)bh * N + lo;  // first token of this piece, over all (b, h)
-  const char* Xb = reinterpret_cast<const char*>(a.x + row0 * D);
-  const char* Vb = reinterpret_cast<const char*>(a.vec + row0 * D);
-  const char* W1 = reinterpret_cast<const char*>(a.w1 + (int64_t)h * HID * D);
-  const bf16_t* W2 = a.w2 + (int64_t)h * DP * HID;
-  char* Ug = reinterpret_cast<char*>(a.U + row0 * HID);
-  bf16_t* Pg = a.dpsi + row0 * DP;
-  const float* Tw = a.tokw ? a.tokw + row0 : nullptr;
+  char* Pg = reinterpret_cast<char*>(a.dpsi + row0 * DP);
 
   // ---- resident operands ----------------------------------------------------
-  float b1lo[16], b1hi[16];
-  {
-    const float* bp = a.b1 + (int64_t)h * HID + wave * 32;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        b1lo[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + j])));
-        b1hi[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + 4 + j])));
-      }
-  }
-  const int unit = wave * 32 + r;  // this lane's feature
+  // first-layer bias in LDS: accumulator register 4i+j is hidden unit 32w + 8i + 4g + j, so a
+  // lane reads its four rows of block i with one 16-byte read
+  if (tid < HID) B1s[tid] = a.b1[(int64_t)h * HID + tid];
+  const float* const b1rows = B1s + wave * 32 + 4 * g;
+  const int unit = wave * 32 + r;  // this lane's hidden unit (first half) and feature (second half)
   const float b2v = a.b2[(int64_t)h * DP + unit];
   const float zvv = a.zv[((int64_t)bh * a.slots + slot) * DP + unit];
+  bf16x8 w1f[KS];   // A operands: row = hidden unit, k = head dimension
+  {
+    const bf16_t* p = a.w1 + ((int64_t)h * HID + unit) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) w1f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
   bf16x8 w2f[KS2];  // B operands: column = feature, k = hidden
   {
-    const bf16_t* p = W2 + (int64_t)unit * HID + 8 * g;
+    const bf16_t* p = a.w2 + ((int64_t)h * DP + unit) * HID + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS2; ++ks) w2f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
   }
@@ -235,83 +242,71 @@ act_grad_kernel(ActGradArgs a) {
     for (int ks = 0; ks < KS; ++ks) mf[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
   }
 
-  const u32x4 Xr = make_rsrc_words(Xb), Vr = make_rsrc_words(Vb), W1r = make_rsrc_words(W1);
-#pragma unroll
-  for (int j = 0; j < HID / 64; ++j)
-    tile_load_asm<2 * D, TB, NW>(W1r, j * TB, lds_address(W1s) + j * TB, wave, lane, 64);
+  const u32x4 Xr = make_rsrc_words(a.x + row0 * D), Vr = make_rsrc_words(a.vec + row0 * D);
+  const u32x4 Twr = make_rsrc_words(TW ? (const void*)(a.tokw + row0) : (const void*)a.x);
+  const uint32_t xv_lds = lds_address(XV), tw_lds = lds_address(Tws);
+  const int voff_full = tile_voff_full<2 * D, NW>(wave, lane);
+  auto issue = [&](int it) {   // tile `it` into the buffers of its parity
+    const int valid = it < n_full ? 64 : rem;
+    const int soff = __builtin_amdgcn_readfirstlane(it * TB);
+    tile_load_fast<2 * D, TB, NW>(Xr, soff, xv_lds + (it & 1) * TB, wave, lane, valid, voff_full);
+    if (TW) {
+      const int t = lane < valid ? lane : valid - 1;
+      direct_load_4(Twr, 4 * t, __builtin_amdgcn_readfirstlane(it * 256), tw_lds + (it & 1) * 256);
+    }
+    tile_load_fast<2 * D, TB, NW>(Vr, soff, xv_lds + (2 + (it & 1)) * TB, wave, lane, valid, voff_full);
+  };
 
   // ---- per-lane LDS byte offsets (as in the chunk-state kernel) -----------------
-  const int hrow = wave * 32 + r;
-  int w1off[KS], xoff[KS];
-#pragma unroll
-  for (int ks = 0; ks < KS; ++ks) {
-    w1off[ks] = (hrow >> 6) * TB + tile_off<2 * D>(hrow & 63, 16 * ks + 8 * g);
-    xoff[ks] = tile_off<2 * D>(r, 16 * ks + 8 * g);
-  }
-  int uwoff[4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i) uwoff[i] = r * UROW + (((wave * 4 + i) ^ swz<256>(r)) << 4) + 8 * g;
-  int uroff[KS2];
-#pragma unroll
-  for (int ks = 0; ks < KS2; ++ks) uroff[ks] = r * UROW + (((2 * ks + g) ^ swz<256>(r)) << 4);
+  // fragment of token row r, k-step ks inside an x or vec tile: chunk 2 ks + g, permuted by the
+  // row -- the chunk bits do not overlap the row bits, so the offset is one XOR away from a
+  // per-lane constant
+  // (derived per tile from an opaque copy of the lane index: held across the loop, the eight
+  // offsets and the addresses of the dpsi patch would push resident operands out of registers)
+  const int uwbase = r * UPAD + wave * 64 + 8 * g;   // write: token r, units 32w + 8i + 4g .. +3 at + 16 i
+  const int urbase = r * UPAD + 16 * g;              // read: A fragment of token r, k-step ks at + 32 ks
+  char* const Sg = Stg + wave * (32 * SROW);   // this wave's patch: [32 tokens][32 features]
 
   float db2acc = 0.f, dzacc = 0.f;
   const bool squared = (wave * 32 >= DP / 2);
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+  if (n_tiles > 0) issue(0);
+  if (n_tiles > 1) {
+    issue(1);
+    wait_loads_and_barrier<LG>();   // tile 0 has landed, tile 1 may be in flight
+  } else {
+    wait_loads_and_barrier<0>();
+  }
+
   for (int it = 0; it < n_tiles; ++it) {
     const int valid = it < n_full ? 64 : rem;
-    const int soff = __builtin_amdgcn_readfirstlane(it * TB);
-    tile_load_asm<2 * D, TB, NW>(Xr, soff, lds_address(Xs), wave, lane, valid);
-    tile_load_asm<2 * D, TB, NW>(Vr, soff, lds_address(Vs), wave, lane, valid);
-    // weights of zv for this lane's accumulator rows (tokens 32 tb + 8 i + 4 g + j)
-    float tw[2][16];
-#pragma unroll
-    for (int tb = 0; tb < 2; ++tb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        int t = 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
-        if (t >= valid) t = valid - 1;
-        tw[tb][e] = Tw ? Tw[it * 64 + t] : 1.0f;
-      }
-    wait_loads_and_barrier<0>();   // tiles (and, on the first pass, W1) have landed
+    const char* const Xs = XV + (it & 1) * TB;
+    const char* const Vs = XV + (2 + (it & 1)) * TB;
+    const float* const tws = Tws + (it & 1) * 64;
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int xbase = tile_off<2 * D>(ln & 31, 8 * (ln >> 5));
 
     // ---- first half ----------------------------------------------------------
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
-      f32x16 u;
-#pragma unroll
-      for (int e = 0; e < 16; ++e) u[e] = g ? b1hi[e] : b1lo[e];
+      f32x16 u = zero;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 wf = *reinterpret_cast<const bf16x8*>(W1s + w1off[ks]);
-        bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + xoff[ks] + tb * (32 * 2 * D));
-        u = mfma(wf, xf, u);
+        bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + (xbase ^ (32 * ks)) + tb * (32 * 2 * D));
+        u = mfma(w1f[ks], xf, u);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
+        const f32x4 bb = *reinterpret_cast<const f32x4*>(b1rows + 8 * i);
         u32x2 pk;
-        pk[0] = pack_bf16(fmaxf(u[4 * i], 0.f), fmaxf(u[4 * i + 1], 0.f));
-        pk[1] = pack_bf16(fmaxf(u[4 * i + 2], 0.f), fmaxf(u[4 * i + 3], 0.f));
-        *reinterpret_cast<u32x2*>(Us + uwoff[i] + tb * (32 * UROW)) = pk;
+        pk[0] = pack_bf16(fmaxf(u[4 * i] + bb[0], 0.f), fmaxf(u[4 * i + 1] + bb[1], 0.f));
+        pk[1] = pack_bf16(fmaxf(u[4 * i + 2] + bb[2], 0.f), fmaxf(u[4 * i + 3] + bb[3], 0.f));
+        *reinterpret_cast<u32x2*>(Us + uwbase + 16 * i + tb * (32 * UPAD)) = pk;
       }
     }
     lds_barrier();   // U complete
-
-    // U tile -> HBM, token-major, 16 bytes per store
-    {
-      constexpr int CPRU = UROW / 16;
-      constexpr int PER = 64 * CPRU / NT;
-#pragma unroll
-      for (int n = 0; n < PER; ++n) {
-        const int idx = tid + n * NT;
-        const int row = idx / CPRU, c = idx % CPRU;
-        if (row < valid) {
-          const u32x4 val = *reinterpret_cast<const u32x4*>(Us + row * UROW + ((c ^ swz<256>(row)) << 4));
-          *reinterpret_cast<u32x4*>(Ug + ((int64_t)it * 64 + row) * UROW + c * 16) = val;
-        }
-      }
-    }
 
     // ---- second half ---------------------------------------------------------
 #pragma unroll
@@ -319,39 +314,53 @@ act_grad_kernel(ActGradArgs a) {
       f32x16 ps = zero, dphi = zero;
 #pragma unroll
       for (int ks = 0; ks < KS2; ++ks) {
-        bf16x8 uf = *reinterpret_cast<const bf16x8*>(Us + uroff[ks] + tb * (32 * UROW));
+        bf16x8 uf = *reinterpret_cast<const bf16x8*>(Us + urbase + 32 * ks + tb * (32 * UPAD));
         ps = mfma(uf, w2f[ks], ps);
       }
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vs + xoff[ks] + tb * (32 * 2 * D));
+        bf16x8 vf = *reinterpret_cast<const bf16x8*>(Vs + (xbase ^ (32 * ks)) + tb * (32 * 2 * D));
         dphi = mfma(vf, mf[ks], dphi);
       }
       float pdb = 0.f, pdz = 0.f;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int t = 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
-        const float psi = fmaxf(ps[e] + b2v, 0.f);
-        float dp = dphi[e] + tw[tb][e] * zvv;          // dL/dPhi
-        float ph = psi;
-        if (squared) {
-          dp = 2.f * psi * dp;                          // Phi = psi^2
-          ph = psi * psi;
-        } else if (!(psi > 0.f)) {
-          dp = 0.f;                                     // Phi = psi = relu(.)
-        }
-        if (t < valid) {
-          pdb += dp;
-          pdz += tw[tb][e] * ph;
-          Pg[((int64_t)it * 64 + t) * DP + unit] = (bf16_t)(pack_bf16(dp, 0.f) & 0xffffu);
+      for (int i = 0; i < 4; ++i) {
+        f32x4 tw = {1.f, 1.f, 1.f, 1.f};   // weights of zv for tokens 32 tb + 8 i + 4 g + j
+        if (TW) tw = *reinterpret_cast<const f32x4*>(tws + 32 * tb + 8 * i + 4 * g);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int e = 4 * i + j;
+          const bool live = 32 * tb + 8 * i + 4 * g + j < valid;
+          const float psi = fmaxf(ps[e] + b2v, 0.f);
+          const float base = dphi[e] + tw[j] * zvv;   // dL/dPhi
+          // Phi = psi^2 in the squared half, psi = relu(.) in the other (wave-uniform choice)
+          const float dp = squared ? 2.f * psi * base : (psi > 0.f ? base : 0.f);
+          const float ph = squared ? psi * psi : psi;
+          pdb += live ? dp : 0.f;
+          pdz += live ? tw[j] * ph : 0.f;
+          *reinterpret_cast<bf16_t*>(Sg + (8 * i + 4 * g + j) * SROW + 2 * r) =
+              (bf16_t)(pack_bf16(dp, 0.f) & 0xffffu);
         }
       }
       db2acc += pdb;
       dzacc += pdz;
+      // the patch leaves token-major: 4 chunks of 16 bytes per token row, two per lane
+#pragma unroll
+      for (int n = 0; n < 2; ++n) {
+        const int idx = ln + 64 * n;
+        const int row = idx >> 2, c = idx & 3;
+        const u32x4 val = *reinterpret_cast<const u32x4*>(Sg + row * SROW + 16 * c);
+        if (32 * tb + row < valid)
+          *reinterpret_cast<u32x4*>(Pg + ((int64_t)it * 64 + 32 * tb + row) * (DP * 2) + wave * 64 + 16 * c) = val;
+      }
     }
-    lds_barrier();   // every wave is done with the tiles and U before the next loads land
+    if (it + 1 < n_tiles) {
+      // tile it+1 has landed: it is older than this (full) tile's NST stores; every wave is done
+      // with this tile's buffers and with U
+      wait_loads_and_barrier<NST>();
+      if (it + 2 < n_tiles) issue(it + 2);
+    }
   }
-  if (n_tiles == 0) wait_loads_and_barrier<0>();   // W1 loads of an empty piece
 
   const float db2 = half_swap_sum(db2acc);
   const float dz = half_swap_sum(dzacc);
@@ -362,8 +371,13 @@ act_grad_kernel(ActGradArgs a) {
 }
 
 hipError_t launch_act_grad(const ActGradArgs& a, int d, int grid, hipStream_t stream) {
-  if (d == 128) hipLaunchKernelGGL((act_grad_kernel<128, 8>), dim3(grid), dim3(512), 0, stream, a);
-  else hipLaunchKernelGGL((act_grad_kernel<64, 4>), dim3(grid), dim3(256), 0, stream, a);
+  if (d == 128) {
+    if (a.tokw) hipLaunchKernelGGL((act_grad_kernel<128, 8, true>), dim3(grid), dim3(512), 0, stream, a);
+    else hipLaunchKernelGGL((act_grad_kernel<128, 8, false>), dim3(grid), dim3(512), 0, stream, a);
+  } else {
+    if (a.tokw) hipLaunchKernelGGL((act_grad_kernel<64, 4, true>), dim3(grid), dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL((act_grad_kernel<64, 4, false>), dim3(grid), dim3(256), 0, stream, a);
+  }
   return hipGetLastError();
 }
 
@@ -384,23 +398,47 @@ __device__ __forceinline__ Piece piece_of(int64_t lo, int64_t hi, int sp, int ns
   return p;
 }
 
+// first-layer bias of the wave's accumulator rows: register 4i+j is hidden unit
+// 32 wave + 8i + 4g + j, two wave-uniform values per register picked by the lane half
+struct BiasRows {
+  float lo[16], hi[16];
+};
+__device__ __forceinline__ BiasRows load_bias_rows(const float* bp) {
+  BiasRows b;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      b.lo[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + j])));
+      b.hi[4 * i + j] = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, bp[8 * i + 4 + j])));
+    }
+  return b;
+}
+
 // ------------------------------------------------------------------------------------
-// dW2 partial: part[f][hid] = sum_tok dpsi[tok][f] U[tok][hid].  Both operands are token-major
-// tiles in LDS read with transposing loads (tokens become the contraction index).  Each
-// wave owns 64 rows f and half of the columns.
+// dW2 partial: part[f][hid] = sum_tok dpsi[tok][f] U[tok][hid].  Per tile the waves first
+// rebuild U = relu(W1 x + b1) in LDS (token-major, as the chunk-state kernel does; 16 MFMAs per
+// wave against 512 bytes per token that U would cost through HBM); then both operands are
+// token-major LDS tiles read with transposing loads (tokens become the contraction index).
+// Each wave owns 64 rows f and half of the columns.  The dpsi and x tiles of tile t+1 are
+// requested at the start of tile t.
 // ------------------------------------------------------------------------------------
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW)
 tn_gemm_kernel(TnGemmArgs a) {
-  constexpr int W = 2 * D;          // columns of X and of Y
-  constexpr int ROWB = 2 * W;       // bytes per token row
-  constexpr int TBY = 64 * ROWB;    // tile bytes
+  constexpr int W = 2 * D;          // features = hidden units
+  constexpr int KS = D / 16;
+  constexpr int ROWB = 2 * W;       // bytes per token row of dpsi and of U
+  constexpr int TBY = 64 * ROWB;    // dpsi tile
+  constexpr int TB = 64 * 2 * D;    // x tile
+  constexpr int SET = TBY + TB;
   constexpr int NT = 64 * NW;
   constexpr int HB = W / 64;        // 32-column blocks per wave (half of the columns)
   static_assert(W / 64 == NW / 2, "waves form a (W/64) x 2 grid");
+  static_assert(W / NW == 32, "each wave rebuilds 32 hidden units");
 
-  __shared__ __attribute__((aligned(1024))) char Xs[TBY];
-  __shared__ __attribute__((aligned(1024))) char Ys[TBY];
+  __shared__ __attribute__((aligned(1024))) char Ts[2 * SET];   // (dpsi tile, x tile) x 2
+  __shared__ __attribute__((aligned(1024))) char Us[TBY];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -412,9 +450,24 @@ tn_gemm_kernel(TnGemmArgs a) {
   if (item >= a.n_items) return;
   const int sp = item % a.nsplit;
   const int bh = item / a.nsplit;
+  const int h = bh % a.H;
   const Piece pc = piece_of(a.lo, a.hi, sp, a.nsplit);
   const int64_t row0 = (int64_t)bh * a.N + pc.tok0;
-  const u32x4 Xr = make_rsrc_words(a.X + row0 * W), Yr = make_rsrc_words(a.Y + row0 * W);
+  const u32x4 Pr = make_rsrc_words(a.dpsi + row0 * W), Xr = make_rsrc_words(a.x + row0 * D);
+
+  const BiasRows b1 = load_bias_rows(a.b1 + (int64_t)h * W + wave * 32);
+  bf16x8 w1f[KS];   // A operands: row = hidden unit 32 wave + r, k = head dimension
+  {
+    const bf16_t* p = a.w1 + ((int64_t)h * W + wave * 32 + r) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) w1f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
+  int xoff[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) xoff[ks] = tile_off<2 * D>(r, 16 * ks + 8 * g);
+  int uwoff[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) uwoff[i] = r * ROWB + (((wave * 4 + i) ^ swz<256>(r)) << 4) + 8 * g;
 
   int xlo[2], xhi[2], ylo[HB], yhi[HB];
 #pragma unroll
@@ -438,35 +491,64 @@ tn_gemm_kernel(TnGemmArgs a) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[fb][hb][e] = 0.f;
 
+  const uint32_t ts_lds = lds_address(Ts);
+  const int pvoff = tile_voff_full<ROWB, NW>(wave, lane), xvoff = tile_voff_full<2 * D, NW>(wave, lane);
+  auto issue = [&](int it) {
+    const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
+    const uint32_t base = ts_lds + (it & 1) * SET;
+    tile_load_fast<ROWB, TBY, NW>(Pr, __builtin_amdgcn_readfirstlane(it * TBY), base, wave, lane, valid, pvoff);
+    tile_load_fast<2 * D, TB, NW>(Xr, __builtin_amdgcn_readfirstlane(it * TB), base + TBY, wave, lane, valid, xvoff);
+  };
+  if (pc.n_tiles > 0) issue(0);
   for (int it = 0; it < pc.n_tiles; ++it) {
     const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
-    const int soff = __builtin_amdgcn_readfirstlane(it * TBY);
-    tile_load_asm<ROWB, TBY, NW>(Xr, soff, lds_address(Xs), wave, lane, valid);
-    tile_load_asm<ROWB, TBY, NW>(Yr, soff, lds_address(Ys), wave, lane, valid);
+    char* const Ps = Ts + (it & 1) * SET;
+    const char* const Xs = Ps + TBY;
+    // tile `it` has landed (the only loads in flight) and every wave is done with tile it-1:
+    // its buffers, which the next request overwrites, and U
     wait_loads_and_barrier<0>();
-    if (valid < 64) {  // rows past the range hold copies of the last row: clear them in X
-      const u32x4 z4 = {0u, 0u, 0u, 0u};
-      for (int o = valid * ROWB + tid * 16; o < TBY; o += NT * 16) *reinterpret_cast<u32x4*>(Xs + o) = z4;
-      lds_barrier();
+    if (it + 1 < pc.n_tiles) issue(it + 1);
+    // U^T slice = relu(W1[slice] X^T + b1[slice]) -> U[token][hidden]
+#pragma unroll
+    for (int tb = 0; tb < 2; ++tb) {
+      f32x16 u;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) u[e] = g ? b1.hi[e] : b1.lo[e];
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + xoff[ks] + tb * (32 * 2 * D));
+        u = mfma(w1f[ks], xf, u);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        u32x2 pk;
+        pk[0] = pack_bf16(fmaxf(u[4 * i], 0.f), fmaxf(u[4 * i + 1], 0.f));
+        pk[1] = pack_bf16(fmaxf(u[4 * i + 2], 0.f), fmaxf(u[4 * i + 3], 0.f));
+        *reinterpret_cast<u32x2*>(Us + uwoff[i] + tb * (32 * ROWB)) = pk;
+      }
     }
+    if (valid < 64) {  // rows past the range hold copies of the last row: clear them in dpsi
+      const u32x4 z4 = {0u, 0u, 0u, 0u};
+      for (int o = valid * ROWB + tid * 16; o < TBY; o += NT * 16) *reinterpret_cast<u32x4*>(Ps + o) = z4;
+    }
+    lds_barrier();   // U (and the cleared rows) complete
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int so = s * 16 * ROWB;
       bf16x8 af[2], bfr[HB];
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb)
-        af[fb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Xs + xlo[fb] + so)),
-                         lds_read_tr(reinterpret_cast<const bf16_t*>(Xs + xhi[fb] + so)));
+        af[fb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Ps + xlo[fb] + so)),
+                         lds_read_tr(reinterpret_cast<const bf16_t*>(Ps + xhi[fb] + so)));
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
-        bfr[hb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Ys + ylo[hb] + so)),
-                          lds_read_tr(reinterpret_cast<const bf16_t*>(Ys + yhi[hb] + so)));
+        bfr[hb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Us + ylo[hb] + so)),
+                          lds_read_tr(reinterpret_cast<const bf16_t*>(Us + yhi[hb] + so)));
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
         for (int hb = 0; hb < HB; ++hb) acc[fb][hb] = mfma(af[fb], bfr[hb], acc[fb][hb]);
     }
-    lds_barrier();
   }
 
   float* P = a.part + (int64_t)item * W * W;
@@ -488,25 +570,26 @@ hipError_t launch_tn_gemm(const TnGemmArgs& a, int d, int grid, hipStream_t stre
 }
 
 // ------------------------------------------------------------------------------------
-// First-layer gradients.  Per tile: dU slice = dpsi W2[:, slice] (tokens in accumulator rows,
-// the wave's 32 hidden units in lanes, W2^T rows resident as B operands), zero where U = 0;
-// then x^T dU into the wave's [d][32] slice of dW1^T, exactly as the chunk-state kernel
-// accumulates V^T phi.
+// First-layer gradients.  Wave w owns hidden units [32w, 32w + 32): its rows of W1 and of
+// W2^T stay in registers as B operands.  Per tile, with tokens in accumulator rows and the
+// wave's hidden units in lanes: U slice = X W1[slice]^T + b1 (only its sign is needed),
+// dU slice = dpsi W2[:, slice], zero where U <= 0; then x^T dU into the wave's [d][32] slice
+// of dW1^T, exactly as the chunk-state kernel accumulates V^T phi.
 // ------------------------------------------------------------------------------------
 template <int D, int NW>
 __global__ void __launch_bounds__(64 * NW)
 hid_grad_kernel(HidGradArgs a) {
   constexpr int HID = 2 * D, DP = 2 * D;
+  constexpr int KS = D / 16;
   constexpr int KS2 = DP / 16;      // k-steps across the features
   constexpr int DB = D / 32;
   constexpr int TB = 64 * 2 * D;    // x tile
-  constexpr int UROW = HID * 2;     // bytes of a dpsi or U row
+  constexpr int UROW = DP * 2;      // bytes of a dpsi row
   constexpr int TBU = 64 * UROW;
+  constexpr int SET = TBU + TB;
   static_assert(HID / NW == 32, "each wave owns 32 hidden units");
 
-  __shared__ __attribute__((aligned(1024))) char Ps[TBU];
-  __shared__ __attribute__((aligned(1024))) char Um[TBU];
-  __shared__ __attribute__((aligned(1024))) char Xs[TB];
+  __shared__ __attribute__((aligned(1024))) char Ts[2 * SET];   // (dpsi tile, x tile) x 2
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -520,26 +603,25 @@ hid_grad_kernel(HidGradArgs a) {
   const int h = bh % a.H;
   const Piece pc = piece_of(a.lo, a.hi, sp, a.nsplit);
   const int64_t row0 = (int64_t)bh * a.N + pc.tok0;
-  const u32x4 Pr = make_rsrc_words(a.dpsi + row0 * DP), Ur = make_rsrc_words(a.U + row0 * HID),
-              Xr = make_rsrc_words(a.x + row0 * D);
+  const u32x4 Pr = make_rsrc_words(a.dpsi + row0 * DP), Xr = make_rsrc_words(a.x + row0 * D);
 
   const int unit = wave * 32 + r;   // this lane's hidden unit
+  const float b1v = a.b1[(int64_t)h * HID + unit];
+  bf16x8 w1f[KS];                   // B operands: column = hidden unit, k = head dimension
+  {
+    const bf16_t* p = a.w1 + ((int64_t)h * HID + unit) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) w1f[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+  }
   bf16x8 w2tf[KS2];                 // B operands: column = hidden unit, k = feature
   {
     const bf16_t* p = a.w2t + ((int64_t)h * HID + unit) * DP + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS2; ++ks) w2tf[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
   }
-  int proff[KS2];
-#pragma unroll
-  for (int ks = 0; ks < KS2; ++ks) proff[ks] = r * UROW + (((2 * ks + g) ^ swz<256>(r)) << 4);
-  int voff_lo[DB], voff_hi[DB];
-#pragma unroll
-  for (int db = 0; db < DB; ++db) {
-    const int col = 32 * db + 16 * (r >> 4) + 4 * (i16 & 3);
-    voff_lo[db] = tile_off<2 * D>(4 * g + (i16 >> 2), col);
-    voff_hi[db] = tile_off<2 * D>(8 + 4 * g + (i16 >> 2), col);
-  }
+  // Fragment offsets inside the tiles are one XOR away from a per-lane constant (the chunk bits
+  // do not overlap the row bits).  They are derived per tile from an opaque copy of the lane
+  // index: held across the loop they would push resident operands out of registers.
 
   f32x16 acc[DB];
 #pragma unroll
@@ -549,30 +631,55 @@ hid_grad_kernel(HidGradArgs a) {
   float dbacc = 0.f;
   const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
+  const uint32_t ts_lds = lds_address(Ts);
+  const int pvoff = tile_voff_full<UROW, NW>(wave, lane), xvoff = tile_voff_full<2 * D, NW>(wave, lane);
+  auto issue = [&](int it) {   // requested one tile step ahead of its use
+    const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
+    const uint32_t base = ts_lds + (it & 1) * SET;
+    tile_load_fast<UROW, TBU, NW>(Pr, __builtin_amdgcn_readfirstlane(it * TBU), base, wave, lane, valid, pvoff);
+    tile_load_fast<2 * D, TB, NW>(Xr, __builtin_amdgcn_readfirstlane(it * TB), base + TBU, wave, lane, valid, xvoff);
+  };
+  if (pc.n_tiles > 0) issue(0);
   for (int it = 0; it < pc.n_tiles; ++it) {
     const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
-    tile_load_asm<UROW, TBU, NW>(Pr, __builtin_amdgcn_readfirstlane(it * TBU), lds_address(Ps), wave, lane, valid);
-    tile_load_asm<UROW, TBU, NW>(Ur, __builtin_amdgcn_readfirstlane(it * TBU), lds_address(Um), wave, lane, valid);
-    tile_load_asm<2 * D, TB, NW>(Xr, __builtin_amdgcn_readfirstlane(it * TB), lds_address(Xs), wave, lane, valid);
+    const char* const Ps = Ts + (it & 1) * SET;
+    const char* const Xs = Ps + TBU;
+    // tile `it` has landed (the only loads in flight) and every wave is done with tile it-1
     wait_loads_and_barrier<0>();
+    if (it + 1 < pc.n_tiles) issue(it + 1);
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int lr = ln & 31, lg = ln >> 5, li = ln & 15;
+    const int pbase = lr * UROW + ((lg ^ swz<256>(lr)) << 4);   // dpsi row lr, chunk 2 ks + g at ^ 32 ks
+    const int xbase = tile_off<2 * D>(lr, 8 * lg);             // x row lr, k-step ks at ^ 32 ks
+    int voff_lo[DB], voff_hi[DB];                              // transposing reads of x
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+      const int col = 32 * db + 16 * (lr >> 4) + 4 * (li & 3);
+      voff_lo[db] = tile_off<2 * D>(4 * lg + (li >> 2), col);
+      voff_hi[db] = tile_off<2 * D>(8 + 4 * lg + (li >> 2), col);
+    }
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
-      f32x16 du = zero;
+      f32x16 uu, du = zero;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) uu[e] = b1v;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        bf16x8 xf = *reinterpret_cast<const bf16x8*>(Xs + (xbase ^ (32 * ks)) + tb * (32 * 2 * D));
+        uu = mfma(xf, w1f[ks], uu);
+      }
 #pragma unroll
       for (int ks = 0; ks < KS2; ++ks) {
-        bf16x8 pf = *reinterpret_cast<const bf16x8*>(Ps + proff[ks] + tb * (32 * UROW));
+        bf16x8 pf = *reinterpret_cast<const bf16x8*>(Ps + (pbase ^ (32 * ks)) + tb * (32 * UROW));
         du = mfma(pf, w2tf[ks], du);
       }
       float part = 0.f;
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int t = 32 * tb + 8 * (e >> 2) + 4 * g + (e & 3);
-        // U[t][unit] from the token-major tile (chunk = unit / 8, permuted by the row)
-        const int sw = ((e & 3) << 2) | ((2 * (e >> 2) + g) & 3);   // swz<256>(t)
-        const uint16_t ub = *reinterpret_cast<const uint16_t*>(
-            Um + t * UROW + ((((unit >> 3) ^ sw)) << 4) + (unit & 7) * 2);
         float x = du[e];
-        if ((ub & 0x7fffu) == 0 || t >= valid) x = 0.f;
+        if (!(uu[e] > 0.f) || t >= valid) x = 0.f;
         x = bf16_round(x);
         du[e] = x;
         part += x;
@@ -590,7 +697,6 @@ hid_grad_kernel(HidGradArgs a) {
         }
       }
     }
-    lds_barrier();
   }
 
   float* P = a.part + (int64_t)item * (D * HID + HID);
@@ -615,7 +721,8 @@ hipError_t launch_hid_grad(const HidGradArgs& a, int d, int grid, hipStream_t st
 // Sum of the per-workgroup partials over batch and pieces, in a fixed order.
 // ------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
-reduce_kernel(ReduceArgs a) {
+reduce_kernel(ReduceJobs jobs) {
+  const ReduceArgs& a = jobs.job[blockIdx.z];
   const int h = blockIdx.y;
   const int i = blockIdx.x * 256 + threadIdx.x;
   const int n = a.R * a.C;
@@ -630,9 +737,12 @@ reduce_kernel(ReduceArgs a) {
   a.out[(int64_t)h * n + o] = acc;
 }
 
-hipError_t launch_reduce(const ReduceArgs& a, hipStream_t stream) {
-  dim3 grid((a.R * a.C + 255) / 256, a.H);
-  hipLaunchKernelGGL(reduce_kernel, grid, dim3(256), 0, stream, a);
+hipError_t launch_reduce(const ReduceJobs& jobs, hipStream_t stream) {
+  int most = 0;
+  for (int j = 0; j < jobs.n; ++j)
+    if (jobs.job[j].R * jobs.job[j].C > most) most = jobs.job[j].R * jobs.job[j].C;
+  dim3 grid((most + 255) / 256, jobs.job[0].H, jobs.n);
+  hipLaunchKernelGGL(reduce_kernel, grid, dim3(256), 0, stream, jobs);
   return hipGetLastError();
 }
 

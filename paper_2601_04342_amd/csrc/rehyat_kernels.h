@@ -150,18 +150,17 @@ struct TransposeArgs {
 
 // Activation gradients of one side (queries or keys): recomputes U = relu(W1 x + b1) and
 // psi = relu(W2 U + b2), forms dPhi = M vec + tokw * zv for the token's segment, and writes
-// U and dpsi = dPhi * dphi/dpsi token-major for the weight-gradient kernels.
+// dpsi = dPhi * dphi/dpsi token-major for the weight-gradient kernels.
 struct ActGradArgs {
   const bf16_t* x;      // [BH, N, d]  q or k
   const bf16_t* vec;    // [BH, N, d]  u (query side) or v (key side)
-  const float* tokw;    // [BH, N] per-token weight of zv, or null for 1
+  const float* tokw;    // [BH, N] per-token weight of zv (query side); unused on the key side (1)
   const bf16_t* w1;
   const float* b1;
   const bf16_t* w2;
   const float* b2;
   const bf16_t* M;      // [BH, slots, dp, d]  S_t (query side) or R_tau (key side)
   const float* zv;      // [BH, slots, dp]     z_t or r_tau
-  bf16_t* U;            // [BH, N, hidden]
   bf16_t* dpsi;         // [BH, N, dp]
   float* db2_part;      // [n_items, dp]  sum over the item's tokens of dpsi
   float* dz_part;       // [n_items, dp]  sum of tokw * phi (query side), or null
@@ -170,21 +169,26 @@ struct ActGradArgs {
   int n_seg, nsplit, slots, n_items, items_per_xcd;
 };
 
-// dW2 partial sums: part[f][hid] = sum over a token range of dpsi[tok][f] * U[tok][hid]
+// dW2 partial sums: part[f][hid] = sum over a token range of dpsi[tok][f] * U[tok][hid], with
+// U = relu(W1 x + b1) recomputed from x (cheaper than moving it through HBM)
 struct TnGemmArgs {
-  const bf16_t* X;      // [BH, N, 2d]  dpsi
-  const bf16_t* Y;      // [BH, N, 2d]  U
+  const bf16_t* dpsi;   // [BH, N, 2d]
+  const bf16_t* x;      // [BH, N, d]
+  const bf16_t* w1;     // [H, 2d, d]
+  const float* b1;      // [H, 2d]
   float* part;          // [BH * nsplit, 2d, 2d]
+  int H;
   int64_t N, lo, hi;    // token range [lo, hi) of every (b, h)
   int nsplit, n_items, items_per_xcd;
 };
 
-// First-layer gradients: dU = (dpsi W2) * [U > 0];  part = x^T dU ([d][hidden]), then the
-// column sums of dU ([hidden])
+// First-layer gradients: dU = (dpsi W2) * [U > 0] with U recomputed from x;
+// part = x^T dU ([d][hidden]), then the column sums of dU ([hidden])
 struct HidGradArgs {
   const bf16_t* dpsi;   // [BH, N, dp]
-  const bf16_t* U;      // [BH, N, hidden]
   const bf16_t* x;      // [BH, N, d]
+  const bf16_t* w1;     // [H, hidden, d]
+  const float* b1;      // [H, hidden]
   const bf16_t* w2t;    // [H, hidden, dp]  W2 transposed
   float* part;          // [BH * nsplit, d*hidden + hidden]
   int H;
@@ -201,6 +205,11 @@ struct ReduceArgs {
   int64_t part_stride, part_off;
   int R, C, transpose;
 };
+// up to four such sums in one launch (one per gradient tensor of a side)
+struct ReduceJobs {
+  ReduceArgs job[4];
+  int n;
+};
 
 hipError_t launch_prep(const PrepArgs& a, hipStream_t stream);
 hipError_t launch_suffix(const SuffixArgs& a, hipStream_t stream);
@@ -208,7 +217,7 @@ hipError_t launch_transpose(const TransposeArgs& a, hipStream_t stream);
 hipError_t launch_act_grad(const ActGradArgs& a, int d, int grid, hipStream_t stream);
 hipError_t launch_tn_gemm(const TnGemmArgs& a, int d, int grid, hipStream_t stream);
 hipError_t launch_hid_grad(const HidGradArgs& a, int d, int grid, hipStream_t stream);
-hipError_t launch_reduce(const ReduceArgs& a, hipStream_t stream);
+hipError_t launch_reduce(const ReduceJobs& jobs, hipStream_t stream);
 hipError_t launch_fill_zero(float* p, int64_t n, hipStream_t stream);
 
 hipError_t launch_state(const StateArgs& a, int d, int grid, hipStream_t stream);
