@@ -438,7 +438,7 @@ tn_gemm_kernel(TnGemmArgs a) {
   static_assert(W / NW == 32, "each wave rebuilds 32 hidden units");
 
   __shared__ __attribute__((aligned(1024))) char Ts[2 * SET];   // (dpsi tile, x tile) x 2
-  __shared__ __attribute__((aligned(1024))) char Us[TBY];
+  __shared__ __attribute__((aligned(1024))) char Us[2 * TBY];   // U of the current and of the next tile
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -493,22 +493,20 @@ tn_gemm_kernel(TnGemmArgs a) {
 
   const uint32_t ts_lds = lds_address(Ts);
   const int pvoff = tile_voff_full<ROWB, NW>(wave, lane), xvoff = tile_voff_full<2 * D, NW>(wave, lane);
-  auto issue = [&](int it) {
-    const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
-    const uint32_t base = ts_lds + (it & 1) * SET;
-    tile_load_fast<ROWB, TBY, NW>(Pr, __builtin_amdgcn_readfirstlane(it * TBY), base, wave, lane, valid, pvoff);
-    tile_load_fast<2 * D, TB, NW>(Xr, __builtin_amdgcn_readfirstlane(it * TB), base + TBY, wave, lane, valid, xvoff);
+  auto valid_of = [&](int it) { return (it + 1 < pc.n_tiles) ? 64 : pc.last_rows; };
+  auto issue_p = [&](int it) {
+    tile_load_fast<ROWB, TBY, NW>(Pr, __builtin_amdgcn_readfirstlane(it * TBY), ts_lds + (it & 1) * SET, wave, lane,
+                                  valid_of(it), pvoff);
   };
-  if (pc.n_tiles > 0) issue(0);
-  for (int it = 0; it < pc.n_tiles; ++it) {
-    const int valid = (it + 1 < pc.n_tiles) ? 64 : pc.last_rows;
-    char* const Ps = Ts + (it & 1) * SET;
-    const char* const Xs = Ps + TBY;
-    // tile `it` has landed (the only loads in flight) and every wave is done with tile it-1:
-    // its buffers, which the next request overwrites, and U
-    wait_loads_and_barrier<0>();
-    if (it + 1 < pc.n_tiles) issue(it + 1);
-    // U^T slice = relu(W1[slice] X^T + b1[slice]) -> U[token][hidden]
+  auto issue_x = [&](int it) {
+    tile_load_fast<2 * D, TB, NW>(Xr, __builtin_amdgcn_readfirstlane(it * TB), ts_lds + (it & 1) * SET + TBY, wave,
+                                  lane, valid_of(it), xvoff);
+  };
+  // U^T slice of tile `it` = relu(W1[slice] X^T + b1[slice]) -> U[token][hidden] in the buffer of
+  // the tile's parity
+  auto build_u = [&](int it) {
+    const char* const Xs = Ts + (it & 1) * SET + TBY;
+    char* const Ud = Us + (it & 1) * TBY;
 #pragma unroll
     for (int tb = 0; tb < 2; ++tb) {
       f32x16 u;
@@ -524,14 +522,34 @@ tn_gemm_kernel(TnGemmArgs a) {
         u32x2 pk;
         pk[0] = pack_bf16(fmaxf(u[4 * i], 0.f), fmaxf(u[4 * i + 1], 0.f));
         pk[1] = pack_bf16(fmaxf(u[4 * i + 2], 0.f), fmaxf(u[4 * i + 3], 0.f));
-        *reinterpret_cast<u32x2*>(Us + uwoff[i] + tb * (32 * ROWB)) = pk;
+        *reinterpret_cast<u32x2*>(Ud + uwoff[i] + tb * (32 * ROWB)) = pk;
       }
     }
+  };
+  // One barrier per tile: in step `it` the waves rebuild U of tile it+1 while they multiply
+  // tile it, so the two phases overlap inside every wave.  x runs one tile ahead of dpsi.
+  if (pc.n_tiles > 0) {
+    issue_x(0);
+    issue_p(0);
+    wait_loads_and_barrier<0>();
+    if (pc.n_tiles > 1) issue_x(1);
+    build_u(0);
+  }
+  for (int it = 0; it < pc.n_tiles; ++it) {
+    const int valid = valid_of(it);
+    char* const Ps = Ts + (it & 1) * SET;
+    const char* const Uc = Us + (it & 1) * TBY;
+    // dpsi of tile `it` and x of tile it+1 have landed (the only loads in flight); U of tile
+    // `it` is complete; every wave is done with tile it-1
+    wait_loads_and_barrier<0>();
+    if (it + 1 < pc.n_tiles) issue_p(it + 1);
+    if (it + 2 < pc.n_tiles) issue_x(it + 2);
     if (valid < 64) {  // rows past the range hold copies of the last row: clear them in dpsi
       const u32x4 z4 = {0u, 0u, 0u, 0u};
       for (int o = valid * ROWB + tid * 16; o < TBY; o += NT * 16) *reinterpret_cast<u32x4*>(Ps + o) = z4;
+      lds_barrier();
     }
-    lds_barrier();   // U (and the cleared rows) complete
+    if (it + 1 < pc.n_tiles) build_u(it + 1);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int so = s * 16 * ROWB;
@@ -542,8 +560,8 @@ tn_gemm_kernel(TnGemmArgs a) {
                          lds_read_tr(reinterpret_cast<const bf16_t*>(Ps + xhi[fb] + so)));
 #pragma unroll
       for (int hb = 0; hb < HB; ++hb)
-        bfr[hb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Us + ylo[hb] + so)),
-                          lds_read_tr(reinterpret_cast<const bf16_t*>(Us + yhi[hb] + so)));
+        bfr[hb] = join_tr(lds_read_tr(reinterpret_cast<const bf16_t*>(Uc + ylo[hb] + so)),
+                          lds_read_tr(reinterpret_cast<const bf16_t*>(Uc + yhi[hb] + so)));
 #pragma unroll
       for (int fb = 0; fb < 2; ++fb)
 #pragma unroll
@@ -720,28 +738,42 @@ hipError_t launch_hid_grad(const HidGradArgs& a, int d, int grid, hipStream_t st
 // ------------------------------------------------------------------------------------
 // Sum of the per-workgroup partials over batch and pieces, in a fixed order.
 // ------------------------------------------------------------------------------------
+// A block owns 64 consecutive elements; four groups of 64 threads each sum every fourth
+// partial, and the four sums are combined in a fixed order.
 __global__ void __launch_bounds__(256)
 reduce_kernel(ReduceJobs jobs) {
+  __shared__ float sums[4][64];
   const ReduceArgs& a = jobs.job[blockIdx.z];
   const int h = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;
+  const int q = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + (threadIdx.x & 63);
   const int n = a.R * a.C;
-  if (i >= n) return;
+  if (blockIdx.x * 64 >= n) return;
   float acc = 0.f;
-  for (int b = 0; b < a.B; ++b) {
-    const float* p = a.part + ((int64_t)(b * a.H + h) * a.per_bh) * a.part_stride + a.part_off + i;
-    for (int s = 0; s < a.per_bh; ++s) acc += p[(int64_t)s * a.part_stride];
+  if (i < n) {
+    const int total = a.B * a.per_bh;
+#pragma unroll 8
+    for (int m = q; m < total; m += 4) {
+      const int b = m / a.per_bh, sidx = m - b * a.per_bh;
+      acc += a.part[((int64_t)(b * a.H + h) * a.per_bh + sidx) * a.part_stride + a.part_off + i];
+    }
   }
-  int o = i;
-  if (a.transpose) o = (i % a.C) * a.R + i / a.C;
-  a.out[(int64_t)h * n + o] = acc;
+  sums[q][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (q == 0 && i < n) {
+    const int e = threadIdx.x;
+    const float tot = ((sums[0][e] + sums[1][e]) + sums[2][e]) + sums[3][e];
+    int o = i;
+    if (a.transpose) o = (i % a.C) * a.R + i / a.C;
+    a.out[(int64_t)h * n + o] = tot;
+  }
 }
 
 hipError_t launch_reduce(const ReduceJobs& jobs, hipStream_t stream) {
   int most = 0;
   for (int j = 0; j < jobs.n; ++j)
     if (jobs.job[j].R * jobs.job[j].C > most) most = jobs.job[j].R * jobs.job[j].C;
-  dim3 grid((most + 255) / 256, jobs.job[0].H, jobs.n);
+  dim3 grid((most + 63) / 64, jobs.job[0].H, jobs.n);
   hipLaunchKernelGGL(reduce_kernel, grid, dim3(256), 0, stream, jobs);
   return hipGetLastError();
 }
