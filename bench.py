@@ -73,6 +73,32 @@ def backward_flops(w, chunk, fwd):
     return dict(forward=fwd["total"], gradient=grad, total=fwd["total"] + grad)
 
 
+def cpu_baseline_backward(w, chunk, q, k, v, phi, G, heads, gpu_grads):
+    """The fp64 gradient oracle on the first `heads` heads of the same workload, timed, then
+    compared entry by entry with what the GPU produced in the timed configuration."""
+    import numpy as np
+    from oracle import grad as ograd
+    qs, ks, vs, gs = (x[:, :heads].double().numpy() for x in (q, k, v, G))
+    ps = {n: p[:heads].double().numpy() for n, p in phi.items()}
+    t0 = time.perf_counter()
+    ref, _ = ograd.phi_backward(qs, ks, vs, ps, gs, w.T, w.HW, chunk, hidden_round="bf16")
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    base = {"value": w.B * w.N * (heads / w.H) / dt, "unit": "tokens/s", "cores": threads,
+            "kind": "oracle", "seconds": round(dt, 3),
+            "sample": f"{heads} of {w.H} heads, all {w.N} tokens, fp64 numpy gradient oracle "
+                      "(forward + gradient); value = layer-equivalent tokens/s"}
+    worst_max, worst_fro = 0.0, 0.0
+    for n, r in ref.items():
+        g = gpu_grads[n][:heads].cpu().double().numpy()
+        worst_max = max(worst_max, float(np.abs(g - r).max() / np.abs(r).max()))
+        worst_fro = max(worst_fro, float(np.linalg.norm(g - r) / np.linalg.norm(r)))
+    parity = {"max_abs_over_max_ref": worst_max, "relative_frobenius": worst_fro,
+              "against": "gradient oracle, every entry of the eight tensors of the sampled heads "
+                         "(worst tensor)"}
+    return base, parity
+
+
 def cpu_baseline(w, chunk, q, k, v, phi, heads, gpu_out):
     """The fp64 oracle, as it stands, on `heads` heads of the same workload, timed; its
     output is then compared with what the GPU produced in the timed configuration."""
@@ -103,6 +129,8 @@ def main():
     ap.add_argument("--workload", default="wan480p")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=12)
+    ap.add_argument("--cpu-heads-backward", type=int, default=4,
+                    help="heads the gradient oracle evaluates in --mode backward (about 1 - 3 s each)")
     ap.add_argument("--mode", choices=("forward", "bidirectional", "stream", "fullsoftmax", "backward"),
                     default="forward",
                     help="forward: rehyat_forward (the headline path); bidirectional: "
@@ -142,7 +170,8 @@ def main():
         step = lambda: binding.forward(dq, dk, dv, dphi, w.T, w.HW, chunk, out=out,
                                        overlap=overlap, causal=False)
     elif args.mode == "backward":
-        dG = synth.make_grad_out(w.B, w.H, w.N, w.d).to("cuda", torch.bfloat16)
+        G = synth.make_grad_out(w.B, w.H, w.N, w.d)
+        dG = G.to("cuda", torch.bfloat16)
         bws = torch.empty(binding.phi_backward_workspace_bytes(w.B, w.H, w.T, w.HW, w.d, chunk),
                           device="cuda", dtype=torch.uint8)
         grads = {n: torch.empty(t.shape, device="cuda", dtype=torch.float32) for n, t in dphi.items()}
@@ -218,6 +247,10 @@ def main():
         # the library's per-kernel events cover forward calls only; rocprofv3 --kernel-trace
         # gives this mode's kernel breakdown
         bf = backward_flops(w, chunk, fl)
+        extra = {}
+        if not args.no_cpu_baseline:
+            extra["cpu_baseline"], extra["parity"] = cpu_baseline_backward(
+                w, chunk, q, k, v, phi, G, min(args.cpu_heads_backward, w.H), grads)
         print(json.dumps({
             "metric": "feature-map gradient step (forward recomputation + backward), tokens/s per layer",
             "value": w.B * w.N / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -229,7 +262,7 @@ def main():
             "algorithmic_tflop": {kk: vv / 1e12 for kk, vv in bf.items()},
             "tflops": bf["total"] / (ms * 1e-3) / 1e12,
             "pct_mfma_peak": 100.0 * bf["total"] / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-            "workspace_bytes": int(bws.numel()), "library_version": binding.version()}))
+            "workspace_bytes": int(bws.numel()), "library_version": binding.version(), **extra}))
         return
     kern_ms = {kk: (tot / n if n else None) for kk, (tot, n) in prof.items()}
     # all launches of the attention kernel in one step share the step's algorithmic work

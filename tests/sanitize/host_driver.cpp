@@ -87,6 +87,32 @@ int main() {
   CHECK(rehyat_step(A, A, A, &phi, nullptr, F, A, 1, 12, 128, 8, 16, 8, 0, nullptr) == REHYAT_E_NULL);
   CHECK(rehyat_step(A, A, A, &phi, F, F, A, 1, 12, 128, 8, 16, 17, 0, nullptr) == REHYAT_E_SHAPE);
   CHECK(rehyat_state(A, A, &phi, F, F, 1, 12, 21, 1560, 128, 22, nullptr) == REHYAT_E_SHAPE);
+  // feature-map gradient: workspace plan arithmetic over a sweep of shapes, then rejections
+  for (int T : {1, 2, 21, 41, 1024})
+    for (int HW : {1, 600, 1560})
+      for (int chunk : {1, 3, INT_MAX})
+        for (int B : {1, 2, 64}) {
+          const size_t wb = rehyat_phi_backward_workspace_bytes(B, 12, T, HW, 128, chunk);
+          CHECK(wb > 0 && wb % 256 == 0);
+          CHECK(wb >= rehyat_phi_backward_workspace_bytes(B, 12, T, HW, 64, chunk));
+        }
+  CHECK(rehyat_phi_backward_workspace_bytes(1, 12, 1025, 1, 128, 1) == 0);
+  CHECK(rehyat_phi_backward_workspace_bytes(1, 12, INT_MAX, INT_MAX, 128, 1) == 0);
+  CHECK(rehyat_phi_backward_workspace_bytes(65535, 65535, 21, 1560, 128, 1) == 0);
+  {
+    rehyat_phi_grads g;
+    g.w1_q = g.b1_q = g.w2_q = g.b2_q = g.w1_k = g.b1_k = g.w2_k = g.b2_k = A;
+    const size_t wb = rehyat_phi_backward_workspace_bytes(1, 12, 21, 1560, 128, 1);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, nullptr, A, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, nullptr, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb - 1, nullptr) == REHYAT_E_WORKSPACE);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, (char*)A + 64, wb, nullptr) == REHYAT_E_WORKSPACE);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 2000, 1, 128, 1, 0, A, (size_t)1 << 40, nullptr) == REHYAT_E_UNSUPPORTED);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, -1, A, wb, nullptr) == REHYAT_E_SHAPE);
+    g.b1_k = nullptr;
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+  }
   CHECK(rehyat_profile_read(nullptr, nullptr) == REHYAT_E_NULL);
   for (int code = 1; code >= -7; --code) CHECK(std::strlen(rehyat_status_string(code)) > 0);
   CHECK(rehyat_version() >= 200);

@@ -202,3 +202,40 @@ def test_noalloc_entry_point_limits():
     assert lib.rehyat_forward_noalloc(A, A, A, P(big), A, 17, 12, 4, 8, 128, 1, None) == binding.E_WORKSPACE
     assert lib.rehyat_forward_noalloc(None, A, A, P(big), A, 1, 12, 4, 8, 128, 1, None) == binding.E_NULL
     assert lib.rehyat_forward_noalloc(A, A, A, P(big), A, 1, 12, 4, 8, 128, 0, None) == binding.E_SHAPE
+
+
+def test_phi_backward_validation_and_workspace_size():
+    """rehyat_phi_backward rejects bad arguments before any GPU work; its workspace grows
+    with the token count (activations are kept token by token) and is 0 for rejected sizes."""
+    lib = binding.library()
+    ok = _phi()
+    P = ctypes.byref
+    g = binding.PhiGrads(*([A] * 8))
+    wsb = lambda *a: lib.rehyat_phi_backward_workspace_bytes(*a)
+    need = wsb(1, 2, 4, 8, 64, 1)
+    assert need > 0 and need % 256 == 0
+    assert wsb(1, 2, 8, 8, 64, 1) > need                 # more tokens, more workspace
+    assert wsb(1, 2, 4, 8, 64, 9) == wsb(1, 2, 4, 8, 64, 4)   # chunk clamps to T
+    assert wsb(1, 2, 4, 8, 96, 1) == 0 and wsb(0, 2, 4, 8, 64, 1) == 0
+    assert wsb(1, 2, 2000, 1, 64, 1) == 0                # more chunks than the entry point takes
+    bw = lambda *a: lib.rehyat_phi_backward(*a)
+    #   q, k, v, phi, grad_out, out, grads, B, H, T, HW, d, chunk, overlap, ws, ws_bytes, stream
+    base = (1, 2, 4, 8, 64, 1, 0)
+    assert bw(A, A, A, P(ok), None, A, P(g), *base, A, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), A, A, None, *base, A, need, None) == binding.E_NULL
+    assert bw(None, A, A, P(ok), A, A, P(g), *base, A, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), A, A, P(g), *base, None, need, None) == binding.E_NULL
+    gn = binding.PhiGrads(*([A] * 8))
+    gn.b2_k = None
+    assert bw(A, A, A, P(ok), A, A, P(gn), *base, A, need, None) == binding.E_NULL
+    gm = binding.PhiGrads(*([A] * 8))
+    gm.w1_q = A + 2
+    assert bw(A, A, A, P(ok), A, A, P(gm), *base, A, need, None) == binding.E_SHAPE
+    assert bw(A, A, A, P(ok), A + 8, A, P(g), *base, A, need, None) == binding.E_SHAPE      # grad_out misaligned
+    assert bw(A, A, A, P(ok), A, A, P(g), *base, A + 16, need, None) == binding.E_WORKSPACE
+    assert bw(A, A, A, P(ok), A, A, P(g), *base, A, need - 1, None) == binding.E_WORKSPACE
+    assert bw(A, A, A, P(ok), A, A, P(g), 1, 2, 4, 8, 64, 1, -1, A, need, None) == binding.E_SHAPE
+    assert bw(A, A, A, P(ok), A, A, P(g), 1, 2, 2000, 1, 64, 1, 0, A, 1 << 40, None) == binding.E_UNSUPPORTED
+    assert bw(A, A, A, P(ok), A, A, P(g), 1, 2, 4, 8, 32, 1, 0, A, need, None) == binding.E_UNSUPPORTED
+    # N at or beyond 2^31 / (4 d): tile offsets of the token-major buffers would not fit 32 bits
+    assert bw(A, A, A, P(ok), A, A, P(g), 1, 1, 1 << 12, 1 << 11, 64, 1 << 12, 0, A, 1 << 40, None) == binding.E_SHAPE
