@@ -993,17 +993,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   char* ws = c.ws;
   const WsLayout& L = c.L;
 
-  // caller's state -> carry
-  StateInArgs in;
-  in.S_in = S;
-  in.z_in = z;
-  in.carry = (float*)(ws + L.carry);
-  in.BH = B * H;
-  in.d = d;
-  in.dprime = dp;
-  hipError_t e = launch_state_in(in, st);
-  if (e != hipSuccess) return hip_fail(e, "state input kernel launch");
-
+  hipError_t e;
   // increment of the tokens that leave the window, in pieces
   int nsplit = 1;
   if (n_absorb > 0) {
@@ -1036,10 +1026,25 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
     e = launch_state(s, d, s.items_per_xcd * 8, st);
     if (e != hipSuccess) return hip_fail(e, "state kernel launch");
   }
-  // slot 0 <- state before the increment (what the read-out uses); carry += increment
-  rc = launch_prefix_window(c, B, H, d, dp, /*n_chunks=*/1, /*n_seg=*/n_absorb > 0 ? 1 : 0, nsplit,
-                            /*first=*/false);
-  if (rc != REHYAT_OK) return rc;
+  // slot 0 <- the caller's state as it is (what the read-out of this chunk uses, Eq. 16); then
+  // the caller's state += the pieces (Eq. 17-18), in place and in its own layout
+  {
+    StepStateArgs ss;
+    ss.S = S;
+    ss.z = z;
+    ss.partial = (const float*)(ws + L.partial);
+    ss.state_s = (bf16_t*)(ws + L.state_s);
+    ss.state_z = (float*)(ws + L.state_z);
+    ss.BH = B * H;
+    ss.d = d;
+    ss.dprime = dp;
+    ss.nsplit = n_absorb > 0 ? nsplit : 0;
+    ss.partial_slots = c.sl.partial;
+    ss.state_slots = c.sl.state;
+    ProfScope prof(true, 1, st);
+    e = launch_step_state(ss, st);
+    if (e != hipSuccess) return hip_fail(e, "step state kernel launch");
+  }
 
   AttnArgs a;
   a.q = (const bf16_t*)q_t;
@@ -1076,16 +1081,6 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   }
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
 
-  // carry -> caller's state
-  StateOutArgs o;
-  o.carry = (const float*)(ws + L.carry);
-  o.S_out = S;
-  o.z_out = z;
-  o.BH = B * H;
-  o.d = d;
-  o.dprime = dp;
-  e = launch_state_out(o, st);
-  if (e != hipSuccess) return hip_fail(e, "state output kernel launch");
   return REHYAT_OK;
 }
 

@@ -100,12 +100,19 @@ struct BidirArgs {
   int elems, s_elems;
 };
 
-// ---- caller's state [dprime][d] + z into the carry layout (inverse of StateOutArgs) ----
-struct StateInArgs {
-  const float* S_in;   // [BH, dprime, d]
-  const float* z_in;   // [BH, dprime]
-  float* carry;        // [BH, d*dprime + dprime]
+// ---- streaming step: the caller's state feeds the read-out and absorbs the step's pieces ----
+// state slot 0 <- the caller's S, z as they are on entry (bf16 S^T [d][dprime] and fp32 z: what
+// Eq. 16 reads for this chunk); then S, z += the pieces the chunk-state kernel wrote (Eq. 17-18),
+// in place, in the caller's layout.
+struct StepStateArgs {
+  float* S;              // [BH, dprime, d]   read and written
+  float* z;              // [BH, dprime]      read and written
+  const float* partial;  // [BH, partial_slots, d*dprime + dprime]: S^T [d][dprime], then z
+  bf16_t* state_s;       // [BH, state_slots, d, dprime]
+  float* state_z;        // [BH, state_slots, dprime]
   int BH, d, dprime;
+  int nsplit;            // pieces to add (0: the state is only copied into slot 0)
+  int partial_slots, state_slots;
 };
 
 // =================================================================================
@@ -226,7 +233,7 @@ hipError_t launch_attn(const AttnArgs& a, int d, int grid, hipStream_t stream);
 int attn_query_tile(int d);  // query tokens per workgroup of the attention kernel
 const char* attn_kernel_name(int d);  // the instance launched for head width d, as profilers show it
 hipError_t launch_state_out(const StateOutArgs& a, hipStream_t stream);
-hipError_t launch_state_in(const StateInArgs& a, hipStream_t stream);
+hipError_t launch_step_state(const StepStateArgs& a, hipStream_t stream);
 hipError_t launch_bidir_state(const BidirArgs& a, hipStream_t stream);
 // S [BH, dprime, d] and z [BH, dprime] <- 0
 hipError_t launch_zero_state(float* S, float* z, int BH, int d, int dprime, hipStream_t stream);

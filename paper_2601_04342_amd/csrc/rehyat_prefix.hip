@@ -89,17 +89,51 @@ state_out_kernel(StateOutArgs a) {
   if (i < a.dprime) a.z_out[(int64_t)bh * a.dprime + i] = c[n + i];
 }
 
+// One tile of 64 features x 16 head-dimension columns of S per block, transposed through LDS
+// both ways: the pieces -- the bulk of the bytes -- and the state slot are moved in 16-byte
+// accesses along the workspace's [d][dprime] rows, the caller's [dprime][d] rows in 64-byte runs.
 __global__ void __launch_bounds__(256)
-state_in_kernel(StateInArgs a) {
-  const int bh = blockIdx.y;
-  const int i = blockIdx.x * 256 + threadIdx.x;  // index into the carry's S^T [d][dprime]
-  const int n = a.d * a.dprime;
-  float* c = a.carry + (int64_t)bh * (n + a.dprime);
-  if (i < n) {
-    const int col = i / a.dprime, e = i % a.dprime;
-    c[i] = a.S_in[(int64_t)bh * n + (int64_t)e * a.d + col];
+step_state_kernel(StepStateArgs a) {
+  __shared__ float tile[64][17];
+  const int bh = blockIdx.z;
+  const int f0 = blockIdx.x * 64, e0 = blockIdx.y * 16;
+  const int tid = threadIdx.x;
+  const int n = a.d * a.dprime, elems = n + a.dprime;
+  float* S = a.S + (int64_t)bh * n;
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int idx = tid + 256 * m, row = idx >> 4, col = idx & 15;
+    tile[row][col] = S[(int64_t)(f0 + row) * a.d + e0 + col];
   }
-  if (i < a.dprime) c[n + i] = a.z_in[(int64_t)bh * a.dprime + i];
+  __syncthreads();
+  const float* part = a.partial + (int64_t)bh * a.partial_slots * elems;
+  bf16_t* slot = a.state_s + (int64_t)bh * a.state_slots * n;
+  {
+    const int f4 = tid & 15, el = tid >> 4;   // features 4 f4 .. 4 f4 + 3 of row e0 + el of S^T
+    const int64_t o = (int64_t)(e0 + el) * a.dprime + f0 + 4 * f4;
+    f32x4 v = {tile[4 * f4][el], tile[4 * f4 + 1][el], tile[4 * f4 + 2][el], tile[4 * f4 + 3][el]};
+    u32x2 pk;
+    pk[0] = pack_bf16(v[0], v[1]);
+    pk[1] = pack_bf16(v[2], v[3]);
+    *reinterpret_cast<u32x2*>(slot + o) = pk;
+#pragma unroll 8
+    for (int sp = 0; sp < a.nsplit; ++sp) v += *reinterpret_cast<const f32x4*>(part + (int64_t)sp * elems + o);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) tile[4 * f4 + i][el] = v[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int m = 0; m < 4; ++m) {
+    const int idx = tid + 256 * m, row = idx >> 4, col = idx & 15;
+    S[(int64_t)(f0 + row) * a.d + e0 + col] = tile[row][col];
+  }
+  if (blockIdx.y == 0 && tid < 64) {   // z of this block's 64 features
+    const int f = f0 + tid;
+    float v = a.z[(int64_t)bh * a.dprime + f];
+    a.state_z[(int64_t)bh * a.state_slots * a.dprime + f] = v;
+    for (int sp = 0; sp < a.nsplit; ++sp) v += part[(int64_t)sp * elems + n + f];
+    a.z[(int64_t)bh * a.dprime + f] = v;
+  }
 }
 
 // s_0 = 0, z_0 = 0 (Eq. 14-15) in the layout of the public state hook
@@ -135,9 +169,9 @@ hipError_t launch_bidir_state(const BidirArgs& a, hipStream_t stream) {
   return hipGetLastError();
 }
 
-hipError_t launch_state_in(const StateInArgs& a, hipStream_t stream) {
-  dim3 grid((a.d * a.dprime + 255) / 256, a.BH);
-  hipLaunchKernelGGL(state_in_kernel, grid, dim3(256), 0, stream, a);
+hipError_t launch_step_state(const StepStateArgs& a, hipStream_t stream) {
+  dim3 grid(a.dprime / 64, a.d / 16, a.BH);
+  hipLaunchKernelGGL(step_state_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 
