@@ -87,6 +87,7 @@ CASES = [
     (1, 2, 6, 700, 128, 1, 0, 2.0),     # many tiles per segment
     (1, 1, 4, 2000, 128, 1, 0, 2.0),    # few (b, h, segment): segments are split
     (1, 2, 40, 20, 64, 1, 0, 3.0),      # many short chunks (segments shorter than a tile)
+    (2, 2, 6, 300, 64, 2, 1, 4.0),      # d = 64 with several tiles per segment, batch 2, overlap
     (1, 1, 2, 1, 128, 1, 0, 1.0),       # two tokens (small phi: with a dominant linear part the
                                         # single query's gradient is a difference of nearly equal terms)
 ]
