@@ -269,6 +269,11 @@ int launch_attn_window(const Ctx& c, const void* q, const void* k, const void* v
   a.stab_mode = stab_mode;
   a.n_items = B * H * n_chunks * qtiles;
   a.items_per_xcd = (a.n_items + 7) / 8;
+  a.n_short = 0;
+  if (c0 == 0 && !bidir && n_chunks > 1) {   // chunk 0 has no read-out phase: its items go last
+    a.n_short = B * H * qtiles;
+    a.items_per_xcd = (a.n_items - a.n_short + 7) / 8 + (a.n_short + 7) / 8;
+  }
   a.q_bh_stride = a.kv_bh_stride = (int64_t)T * HW * d;
   a.step_nq = a.step_nwin = 0;
   a.all_linear = bidir ? 1 : 0;
@@ -1075,6 +1080,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   a.step_nq = n_q;
   a.step_nwin = n_win;
   a.all_linear = 0;
+  a.n_short = 0;
   {
     ProfScope prof(true, 2, st);
     e = launch_attn(a, d, a.items_per_xcd * 8, st);

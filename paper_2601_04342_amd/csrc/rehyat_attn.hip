@@ -318,13 +318,37 @@ attn_kernel(AttnArgs a) {
   const int r = lane & 31;
 
   // ---- which work item -------------------------------------------------
-  const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);
-  if (item >= a.n_items) return;
-  // item = (bh * n_win_chunks + tc) * qtiles + qt, qt fastest
-  const int qt = item % a.qtiles;
-  const int rest = item / a.qtiles;
-  const int tc = rest % a.n_win_chunks;
-  const int bh = rest / a.n_win_chunks;
+  int qt, tc, bh;
+  if (a.n_short == 0) {
+    const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);
+    if (item >= a.n_items) return;
+    // item = (bh * n_win_chunks + tc) * qtiles + qt, qt fastest
+    qt = item % a.qtiles;
+    const int rest = item / a.qtiles;
+    tc = rest % a.n_win_chunks;
+    bh = rest / a.n_win_chunks;
+  } else {
+    // The window starts at chunk 0, whose items have no read-out phase and are the shortest:
+    // every XCD runs its share of them last, so that the launch does not end on long items.
+    const int xcd = blockIdx.x & 7, i = blockIdx.x >> 3;
+    const int n_long = a.n_items - a.n_short;
+    const int per_long = (n_long + 7) / 8, per_short = (a.n_short + 7) / 8;
+    if (i < per_long) {
+      const int li = xcd * per_long + i;
+      if (li >= n_long) return;
+      const int per_bh = (a.n_win_chunks - 1) * a.qtiles;
+      bh = li / per_bh;
+      const int rest = li % per_bh;
+      tc = 1 + rest / a.qtiles;
+      qt = rest % a.qtiles;
+    } else {
+      const int si = xcd * per_short + (i - per_long);
+      if (si >= a.n_short) return;
+      bh = si / a.qtiles;
+      tc = 0;
+      qt = si % a.qtiles;
+    }
+  }
   const int t = a.chunk0 + tc;
   const int h = bh % a.H;
   ChunkRange cr;

@@ -68,6 +68,9 @@ struct AttnArgs {
   int state_slots;
   int stab_mode;
   int n_items, items_per_xcd;
+  int n_short;           // > 0: the window's first chunk is chunk 0 (no linear part); its n_short
+                         // = BH * qtiles items run last on every XCD (items_per_xcd then counts
+                         // ceil(long / 8) + ceil(short / 8))
   int64_t q_bh_stride;   // elements between the q (and out) rows of consecutive (b, h)
   int64_t kv_bh_stride;  // same for k and v
   int step_nq, step_nwin;  // step_nq > 0 (streaming step): queries are rows [0, step_nq) of q,

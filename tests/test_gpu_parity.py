@@ -20,7 +20,7 @@ def _announce(request):
 
 
 def test_tiny_baseline_config_with_components():
-    """BASELINE config 1: B=1, H=2, d=64, T=4 x 8x8 tokens, chunk 1; q, k, v
+    """The tiny benchmark configuration: B=1, H=2, d=64, T=4 x 8x8 tokens, chunk 1; q, k, v
     seed 0, phi seed 1."""
     w = synth.WORKLOADS["tiny"]
     q, k, v, phi = synth.make_workload(w)

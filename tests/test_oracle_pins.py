@@ -164,7 +164,7 @@ def test_recurrent_form_equals_brute_force(case, causal, stab):
 
 
 def test_tiny_baseline_config_recurrent_equals_brute():
-    """BASELINE config 1 (B=1, H=2, d=64, T=4, 8x8 tokens, chunk 1)."""
+    """The tiny benchmark configuration (B=1, H=2, d=64, T=4, 8x8 tokens, chunk 1)."""
     w = synth.WORKLOADS["tiny"]
     q, k, v, phi = synth.make_workload(w)
     q, k, v = (x.double().numpy() for x in (q, k, v))
