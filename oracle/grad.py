@@ -22,7 +22,8 @@ followed by the backward pass of the two-layer map phi = [psi_1, psi_2^2],
 psi = relu(W2 u + b2), u = relu(W1 x + b1) ("Characterization of phi", appendix
 "Training Details").  The stabiliser reading (per-row maximum) and the ReLU are the
 readings of the forward oracle; "parity unpinned" applies to them exactly as there.
-This function itself is pinned by central finite differences of the forward oracle
+This function itself is pinned by central finite differences of the forward oracle and,
+entry by entry, by reverse-mode differentiation of the token-by-token definition
 (tests/test_oracle_grad_pins.py).
 
 ReLU gates are 0/1 decisions taken by floating point.  A kernel that keeps the hidden

@@ -146,3 +146,47 @@ def test_bf16_rounding_helper_and_hidden_round_option():
     assert np.array_equal(y0, y1)
     for name in NAMES:
         assert np.array_equal(g0[name], g1[name])
+
+
+@pytest.mark.parametrize("T,HW,chunk,overlap", [(4, 5, 1, 0), (5, 4, 2, 1), (6, 3, 2, 0)])
+def test_every_entry_against_reverse_mode_differentiation_of_the_definition(T, HW, chunk, overlap):
+    """Eq. 5-9 with the sets of Eq. 12-13 written token by token in torch (fp64) and
+    differentiated by torch's reverse mode: every entry of all eight gradients, not a sample.
+    The library routine knows nothing of the chunk-wise derivation in oracle/grad.py."""
+    import torch
+    B, H, d, hidden, dprime = 1, 2, 6, 10, 8
+    q, k, v, phi, G = make(B, H, T, HW, d, hidden, dprime, seed=77 + T)
+    tq, tk, tv, tG = (torch.tensor(a, dtype=torch.float64) for a in (q, k, v, G))
+    tp = {n: torch.tensor(a, dtype=torch.float64, requires_grad=True) for n, a in phi.items()}
+
+    def fmap(x, s, h):
+        u = torch.relu(tp[f"w1_{s}"][h] @ x + tp[f"b1_{s}"][h])
+        psi = torch.relu(tp[f"w2_{s}"][h] @ u + tp[f"b2_{s}"][h])
+        half = dprime // 2
+        return torch.cat([psi[:half], psi[half:] ** 2])
+
+    loss = torch.zeros((), dtype=torch.float64)
+    N = T * HW
+    for b in range(B):
+        for h in range(H):
+            fk = [fmap(tk[b, h, j], "k", h) for j in range(N)]
+            for i in range(N):
+                t = i // (chunk * HW)
+                q_lo = t * chunk * HW
+                q_hi = min((t + 1) * chunk, T) * HW
+                s_lo = max(q_lo - overlap * HW, 0)
+                scores = torch.stack([tq[b, h, i] @ tk[b, h, j] for j in range(s_lo, q_hi)]) / d ** 0.5
+                w = torch.exp(scores - scores.max())
+                num = (w[:, None] * tv[b, h, s_lo:q_hi]).sum(0)
+                den = w.sum()
+                if s_lo > 0:
+                    fq = fmap(tq[b, h, i], "q", h)
+                    lw = torch.stack([fq @ fk[j] for j in range(s_lo)])
+                    num = num + (lw[:, None] * tv[b, h, :s_lo]).sum(0)
+                    den = den + lw.sum()
+                loss = loss + (tG[b, h, i] * num / den).sum()
+    loss.backward()
+    grads, _ = grad.phi_backward(q, k, v, phi, G, T, HW, chunk, overlap)
+    for name in NAMES:
+        want = tp[name].grad.numpy()
+        assert np.abs(grads[name] - want).max() <= 1e-10 * max(1.0, np.abs(want).max()), name
