@@ -433,7 +433,7 @@ struct BwdPlan {
   int nc, n_seg;     // chunks; segments (= chunks that read a state)
   int nsplit;        // pieces per segment (state and activation-gradient kernels)
   int nsplit_g;      // pieces per (b, h) of the weight-gradient kernels
-  size_t yhat, nS, nL, u, tokw, Sn, Rt, Rn, rz, w2t_q, w2t_k, dpsi, p_w2, p_w1, p_b2, p_dz, total;
+  size_t yhat, nS, nL, u, tokw, Rt, rz, w2t_q, w2t_k, dpsi, p_w2, p_w1, p_b2, p_dz, total;
 };
 
 BwdPlan bwd_plan(int B, int H, int T, int HW, int d, int chunk) {
@@ -462,9 +462,7 @@ BwdPlan bwd_plan(int B, int H, int T, int HW, int d, int chunk) {
   P.nL = take(BH * N * sizeof(float));
   P.u = take(BH * N * d * sizeof(bf16_t));
   P.tokw = take(BH * N * sizeof(float));
-  P.Sn = take(BH * P.nc * (size_t)dp * d * sizeof(bf16_t));
   P.Rt = take(BH * P.nc * (size_t)dp * d * sizeof(bf16_t));
-  P.Rn = take(BH * P.nc * (size_t)dp * d * sizeof(bf16_t));
   P.rz = take(BH * P.nc * (size_t)dp * sizeof(float));
   P.w2t_q = take((size_t)H * hid * dp * sizeof(bf16_t));
   P.w2t_k = take((size_t)H * hid * dp * sizeof(bf16_t));
@@ -828,23 +826,14 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
   if (rc != REHYAT_OK) return rc;
 
   hipError_t e;
-  TransposeArgs tr;
-  tr.in = (const bf16_t*)(ws + P.F.state_s);   // S_t^T [d][dp] -> S_t [dp][d]
-  tr.out = (bf16_t*)(ws + P.Sn);
-  tr.n = BH * nc;
-  tr.R = d;
-  tr.C = dp;
-  e = launch_transpose(tr, st);
-  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
-  tr.n = H;   // W2 [dp][hidden] -> [hidden][dp]
+  TransposeArgs tr;   // W2 [dp][hidden] -> [hidden][dp] of both maps
+  tr.n = H;
   tr.R = dp;
   tr.C = hid;
   tr.in = (const bf16_t*)phi->w2_q;
   tr.out = (bf16_t*)(ws + P.w2t_q);
-  e = launch_transpose(tr, st);
-  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
-  tr.in = (const bf16_t*)phi->w2_k;
-  tr.out = (bf16_t*)(ws + P.w2t_k);
+  tr.in2 = (const bf16_t*)phi->w2_k;
+  tr.out2 = (bf16_t*)(ws + P.w2t_k);
   e = launch_transpose(tr, st);
   if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
 
@@ -894,7 +883,7 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
                 (float*)grads->w1_q, (float*)grads->b1_q, (float*)grads->w2_q, (float*)grads->b2_q};
   const ChunkRange c1 = chunk_range(T, HW, chunk, overlap, 1);
   rc = backward_side(ws, P, st, q, ws + P.u, (const float*)(ws + P.tokw), sq,
-                     (const bf16_t*)(ws + P.w2t_q), (const bf16_t*)(ws + P.Sn),
+                     (const bf16_t*)(ws + P.w2t_q), (const bf16_t*)(ws + P.F.state_s),
                      (const float*)(ws + P.F.state_z), true, (float*)(ws + P.p_dz), B, H, T, HW, d,
                      chunk, overlap, c1.q_lo, N);
   if (rc != REHYAT_OK) return rc;
@@ -916,20 +905,13 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
   sa.dp = dp;
   e = launch_suffix(sa, st);
   if (e != hipSuccess) return hip_fail(e, "suffix kernel launch");
-  tr.in = (const bf16_t*)(ws + P.Rt);
-  tr.out = (bf16_t*)(ws + P.Rn);
-  tr.n = BH * nc;
-  tr.R = d;
-  tr.C = dp;
-  e = launch_transpose(tr, st);
-  if (e != hipSuccess) return hip_fail(e, "transpose kernel launch");
 
   // ---- key side ------------------------------------------------------------------------
   SideParams sk{phi->w1_k, phi->b1_k, phi->w2_k, phi->b2_k,
                 (float*)grads->w1_k, (float*)grads->b1_k, (float*)grads->w2_k, (float*)grads->b2_k};
   const ChunkRange cl = chunk_range(T, HW, chunk, overlap, nc - 1);
   return backward_side(ws, P, st, k, v, nullptr, sk, (const bf16_t*)(ws + P.w2t_k),
-                       (const bf16_t*)(ws + P.Rn), (const float*)(ws + P.rz), false, nullptr, B, H, T,
+                       (const bf16_t*)(ws + P.Rt), (const float*)(ws + P.rz), false, nullptr, B, H, T,
                        HW, d, chunk, overlap, 0, cl.s_lo);
 }
 

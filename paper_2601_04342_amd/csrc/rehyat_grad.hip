@@ -111,16 +111,24 @@ hipError_t launch_suffix(const SuffixArgs& a, hipStream_t stream) {
 }
 
 // ------------------------------------------------------------------------------------
-// bf16 [n][R][C] -> [n][C][R] through a padded 32 x 32 LDS tile.
+// bf16 [n][R][C] -> [n][C][R] through a padded 32 x 32 LDS tile; optionally a second batch of n
+// matrices of the same shape in the same launch.
 // ------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 transpose_kernel(TransposeArgs a) {
   __shared__ bf16_t tile[32][33];
-  const int m = blockIdx.z;
+  int m = blockIdx.z;
+  const bf16_t* in = a.in;
+  bf16_t* out = a.out;
+  if (m >= a.n) {   // second batch of matrices
+    m -= a.n;
+    in = a.in2;
+    out = a.out2;
+  }
   const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
   const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-  const bf16_t* in = a.in + (int64_t)m * a.R * a.C;
-  bf16_t* out = a.out + (int64_t)m * a.R * a.C;
+  in += (int64_t)m * a.R * a.C;
+  out += (int64_t)m * a.R * a.C;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int rr = r0 + ty + 8 * j, cc = c0 + tx;
@@ -135,7 +143,7 @@ transpose_kernel(TransposeArgs a) {
 }
 
 hipError_t launch_transpose(const TransposeArgs& a, hipStream_t stream) {
-  dim3 grid((a.C + 31) / 32, (a.R + 31) / 32, a.n);
+  dim3 grid((a.C + 31) / 32, (a.R + 31) / 32, a.in2 ? 2 * a.n : a.n);
   hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, stream, a);
   return hipGetLastError();
 }
@@ -237,9 +245,20 @@ act_grad_kernel(ActGradArgs a) {
   }
   bf16x8 mf[KS];    // B operands: column = feature, k = head dimension (row `unit` of M)
   {
-    const bf16_t* p = a.M + (((int64_t)bh * a.slots + slot) * DP + unit) * D + 8 * g;
+    // M is stored transposed ([d][dprime], the layout of the forward chunk states): the eight
+    // values of a fragment are gathered one by one -- once per workgroup
+    const bf16_t* p = a.M + ((int64_t)bh * a.slots + slot) * D * DP + unit;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) mf[ks] = *reinterpret_cast<const bf16x8*>(p + 16 * ks);
+    for (int ks = 0; ks < KS; ++ks) {
+      u32x4 w;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const uint32_t lo = p[(int64_t)(16 * ks + 8 * g + 2 * j) * DP];
+        const uint32_t hi = p[(int64_t)(16 * ks + 8 * g + 2 * j + 1) * DP];
+        w[j] = lo | (hi << 16);
+      }
+      mf[ks] = __builtin_bit_cast(bf16x8, w);
+    }
   }
 
   const u32x4 Xr = make_rsrc_words(a.x + row0 * D), Vr = make_rsrc_words(a.vec + row0 * D);

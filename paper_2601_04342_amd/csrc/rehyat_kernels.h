@@ -145,16 +145,18 @@ struct PrepArgs {
 struct SuffixArgs {
   const float* s_part;  // [BH, s_slots, elems]: segment s, piece p at slot s*s_nsplit + p; S^T part used
   const float* z_part;  // [(bh*n_seg + s)*z_nsplit + p][dp]
-  bf16_t* Rt;           // [BH, slots, d, dp]  (transposed, as the forward states)
+  bf16_t* Rt;           // [BH, slots, d, dp]  (transposed, as the forward chunk states)
   float* r;             // [BH, slots, dp]
   int BH, n_seg, s_nsplit, s_slots, z_nsplit, slots;
   int elems, s_elems, dp;
 };
 
-// bf16 matrices [n][R][C] -> [n][C][R]
+// bf16 matrices [n][R][C] -> [n][C][R]; in2/out2 (nullable): a second batch of n such matrices
 struct TransposeArgs {
   const bf16_t* in;
   bf16_t* out;
+  const bf16_t* in2;
+  bf16_t* out2;
   int n, R, C;
 };
 
@@ -169,7 +171,7 @@ struct ActGradArgs {
   const float* b1;
   const bf16_t* w2;
   const float* b2;
-  const bf16_t* M;      // [BH, slots, dp, d]  S_t (query side) or R_tau (key side)
+  const bf16_t* M;      // [BH, slots, d, dp]  S_t (query side) or R_tau (key side), transposed
   const float* zv;      // [BH, slots, dp]     z_t or r_tau
   bf16_t* dpsi;         // [BH, N, dp]
   float* db2_part;      // [n_items, dp]  sum over the item's tokens of dpsi
