@@ -220,10 +220,13 @@ int rehyat_forward_noalloc(const void *q, const void *k, const void *v,
  *             [H, dprime] for each map), summed over the batch; overwritten
  *   workspace DEVICE, 256-byte aligned, at least
  *             rehyat_phi_backward_workspace_bytes(...) bytes.  Unlike the
- *             forward workspace it grows with N: the hidden activations and
- *             their gradients are kept token by token (about 2.3 KB per token
- *             and head at d = 128).  Used only for the duration of the
- *             enqueued work; no library state is touched.
+ *             forward workspace it grows with N: y_hat, dL/dy_hat / den and
+ *             the gradient of the second layer's pre-activations are kept
+ *             token by token (about 1 KB per token and head at d = 128), beside
+ *             the per-workgroup partial sums of the weight gradients (about
+ *             0.2 GB at d = 128 whenever B*H does not exceed 256).  Used only
+ *             for the duration of the enqueued work; no library state is
+ *             touched.
  *
  * Sums over tokens run in a fixed order: results are bit-reproducible.
  * Supported: d in {64, 128}, hidden = dprime = 2 d, degree 2, at most
