@@ -16,10 +16,13 @@ pytestmark = pytest.mark.gpu
 # six roundings of relative size <= 2^-8 (rms 2^-9 / sqrt 3 = 1.1e-3) along one path, fp32
 # accumulation.  The terms of a sum have random signs, so the relative error of the sum stays at
 # the level of one term's: about sqrt(6) * 1.1e-3 = 2.8e-3 in the Frobenius norm (4e-3 to 5e-3 when
-# the roundings are replayed in numpy on the first cases below); the bars leave a factor two
-# to four.  The hidden activations U are bf16 on both sides (hidden_round of the oracle), so
+# the roundings are replayed in numpy on the first cases below): the Frobenius bar leaves a factor
+# two.  The largest single-entry error is the maximum over 10^4 - 10^6 entries of a roughly Gaussian
+# error of that relative size, i.e. 4 - 5 standard deviations of an entry (1.6e-2 of max |ref| is the
+# largest seen, on a 320x480 workload); its bar is set at six.  A wrong term, sign or index moves
+# entries by O(1).  The hidden activations U are bf16 on both sides (hidden_round of the oracle), so
 # the ReLU gates of the second layer are decided on the same values.
-MAX_REL = 2e-2    # max |gpu - ref| <= MAX_REL * max |ref|
+MAX_REL = 3e-2    # max |gpu - ref| <= MAX_REL * max |ref|
 FRO_REL = 1e-2    # ||gpu - ref||_F <= FRO_REL * ||ref||_F
 
 
