@@ -213,8 +213,16 @@ int rehyat_forward_noalloc(const void *q, const void *k, const void *v,
  *
  *   q, k, v, phi_params, B, H, T, HW, d, chunk, overlap : as rehyat_forward_ex
  *   grad_out  [B, H, N, d] bf16 DEVICE  G
- *   out       [B, H, N, d] bf16 DEVICE, nullable: receives y_hat of the
- *             recomputed forward pass
+ *   out       [B, H, N, d] bf16 DEVICE.  With saved == NULL: nullable, receives
+ *             y_hat of the recomputed forward pass.  With saved != NULL: input,
+ *             y_hat as rehyat_forward_ex wrote it for the same arguments.
+ *   saved     HOST struct, nullable.  A distillation step has already run the
+ *             forward pass to form the loss; passing what it produced -- `out`
+ *             and the components nS, nL [B, H, N] fp32 (DEVICE) of
+ *             rehyat_debug_out, stabiliser REHYAT_STAB_ROWMAX -- skips the
+ *             fused attention kernel here (the chunk states are still rebuilt:
+ *             the forward workspace does not keep them).  NULL recomputes
+ *             everything.
  *   grads     HOST struct of DEVICE pointers, fp32, same shapes as the
  *             parameters ([H, hidden, d], [H, hidden], [H, dprime, hidden],
  *             [H, dprime] for each map), summed over the batch; overwritten
@@ -234,18 +242,23 @@ int rehyat_forward_noalloc(const void *q, const void *k, const void *v,
  * 2^31 / (4 d).  One chunk (chunk >= T) gives all-zero gradients.
  * rehyat_phi_backward_workspace_bytes returns 0 for sizes the call rejects.
  * Errors: as rehyat_forward_ex, plus REHYAT_E_NULL (grad_out, grads, one of its
- * pointers, or workspace NULL) and REHYAT_E_WORKSPACE.
+ * pointers, workspace, or -- with saved -- out, nS or nL NULL) and
+ * REHYAT_E_WORKSPACE.
  */
 #define REHYAT_BACKWARD_MAX_CHUNKS 1024
 typedef struct {
   void *w1_q, *b1_q, *w2_q, *b2_q;
   void *w1_k, *b1_k, *w2_k, *b2_k;
 } rehyat_phi_grads;
+typedef struct {
+  const float *nS, *nL;
+} rehyat_forward_saved;
 size_t rehyat_phi_backward_workspace_bytes(int B, int H, int T, int HW, int d,
                                            int chunk);
 int rehyat_phi_backward(const void *q, const void *k, const void *v,
                         const rehyat_phi_params *phi_params,
                         const void *grad_out, void *out,
+                        const rehyat_forward_saved *saved,
                         const rehyat_phi_grads *grads, int B, int H, int T,
                         int HW, int d, int chunk, int overlap, void *workspace,
                         size_t workspace_bytes, void *stream);

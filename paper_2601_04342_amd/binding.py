@@ -43,6 +43,10 @@ class PhiGrads(ctypes.Structure):
                 ("w1_q", "b1_q", "w2_q", "b2_q", "w1_k", "b1_k", "w2_k", "b2_k")]
 
 
+class ForwardSaved(ctypes.Structure):
+    _fields_ = [("nS", ctypes.c_void_p), ("nL", ctypes.c_void_p)]
+
+
 BACKWARD_MAX_CHUNKS = 1024
 
 
@@ -99,8 +103,8 @@ def _load():
     lib.rehyat_phi_backward_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
     lib.rehyat_phi_backward.restype = ci
     lib.rehyat_phi_backward.argtypes = [vp, vp, vp, ctypes.POINTER(PhiParams), vp, vp,
-                                        ctypes.POINTER(PhiGrads), ci, ci, ci, ci, ci, ci, ci,
-                                        vp, ctypes.c_size_t, vp]
+                                        ctypes.POINTER(ForwardSaved), ctypes.POINTER(PhiGrads),
+                                        ci, ci, ci, ci, ci, ci, ci, vp, ctypes.c_size_t, vp]
     lib.rehyat_shutdown.restype = ci
     lib.rehyat_shutdown.argtypes = []
     lib.rehyat_status_string.restype = ctypes.c_char_p
@@ -339,13 +343,14 @@ def phi_backward_workspace_bytes(B, H, T, HW, d, chunk):
 
 
 def phi_backward(q, k, v, phi, grad_out, T, HW, chunk, overlap=0, workspace=None, out=None,
-                 grads=None, stream=None):
+                 grads=None, stream=None, saved=None):
     """Gradients of a loss w.r.t. the parameters of phi_q and phi_k for a given
     ``grad_out`` = dL/dy_hat (CUDA bf16 [B, H, T*HW, d]): one step of the distillation of
     Eq. 19.  Returns ``(grads, y_hat)``: a dict of eight fp32 CUDA tensors shaped like the
     parameters, and the output of the recomputed forward pass.  ``workspace`` is a CUDA
     byte tensor of at least ``phi_backward_workspace_bytes`` bytes (allocated here if
-    None)."""
+    None).  ``saved`` = (out, nS, nL) from ``forward(..., debug=True)`` on the same arguments
+    skips the attention kernel of the recomputation."""
     lib = _load()
     _check_qkv(q, k, v)
     if grad_out.shape != q.shape or grad_out.dtype != torch.bfloat16 or not grad_out.is_cuda \
@@ -362,6 +367,15 @@ def phi_backward(q, k, v, phi, grad_out, T, HW, chunk, overlap=0, workspace=None
         if need == 0:
             raise RehyatError(E_UNSUPPORTED, "rehyat_phi_backward_workspace_bytes")
         workspace = torch.empty(need, device=q.device, dtype=torch.uint8)
+    sv = None
+    if saved is not None:
+        out, nS, nL = saved
+        for t in (nS, nL):
+            if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous() or t.shape != q.shape[:3]:
+                raise TypeError("saved nS, nL must be contiguous CUDA fp32 tensors [B, H, N]")
+        if out.shape != q.shape or out.dtype != torch.bfloat16 or not out.is_contiguous():
+            raise TypeError("saved out must match q")
+        sv = ForwardSaved(nS.data_ptr(), nL.data_ptr())
     if out is None:
         out = torch.empty_like(q)
     if grads is None:
@@ -374,7 +388,8 @@ def phi_backward(q, k, v, phi, grad_out, T, HW, chunk, overlap=0, workspace=None
         setattr(g, name, t.data_ptr())
     s = torch.cuda.current_stream() if stream is None else stream
     rc = lib.rehyat_phi_backward(q.data_ptr(), k.data_ptr(), v.data_ptr(), ctypes.byref(p),
-                                 grad_out.data_ptr(), out.data_ptr(), ctypes.byref(g),
+                                 grad_out.data_ptr(), out.data_ptr(),
+                                 ctypes.byref(sv) if sv is not None else None, ctypes.byref(g),
                                  B, H, T, HW, d, chunk, overlap, workspace.data_ptr(),
                                  workspace.numel() * workspace.element_size(),
                                  ctypes.c_void_p(s.cuda_stream))

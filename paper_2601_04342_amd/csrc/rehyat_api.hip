@@ -757,10 +757,12 @@ size_t rehyat_phi_backward_workspace_bytes(int B, int H, int T, int HW, int d, i
 }
 
 int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehyat_phi_params* phi,
-                        const void* grad_out, void* out, const rehyat_phi_grads* grads, int B,
-                        int H, int T, int HW, int d, int chunk, int overlap, void* workspace,
-                        size_t workspace_bytes, void* stream) {
+                        const void* grad_out, void* out, const rehyat_forward_saved* saved,
+                        const rehyat_phi_grads* grads, int B, int H, int T, int HW, int d, int chunk,
+                        int overlap, void* workspace, size_t workspace_bytes, void* stream) {
   if (!grad_out || !grads) return REHYAT_E_NULL;
+  if (saved && (!out || !saved->nS || !saved->nL)) return REHYAT_E_NULL;
+  if (saved && (!aligned4(saved->nS) || !aligned4(saved->nL))) return REHYAT_E_SHAPE;
   int rc = validate_forward(q, k, v, phi, out ? out : grad_out, B, H, T, HW, d, &chunk, &overlap, 1,
                             REHYAT_STAB_ROWMAX);
   if (rc != REHYAT_OK) return rc;
@@ -799,9 +801,11 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
 
   if (nc == 1) {
     // one chunk: plain softmax attention (Eq. 2), independent of phi -- all gradients are zero
-    rc = launch_attn_window(c, q, k, v, phi, y, nullptr, B, H, T, HW, d, chunk, overlap, 0, 1, qtiles,
-                            REHYAT_STAB_ROWMAX, false);
-    if (rc != REHYAT_OK) return rc;
+    if (!saved) {
+      rc = launch_attn_window(c, q, k, v, phi, y, nullptr, B, H, T, HW, d, chunk, overlap, 0, 1, qtiles,
+                              REHYAT_STAB_ROWMAX, false);
+      if (rc != REHYAT_OK) return rc;
+    }
     float* gp[8] = {(float*)grads->w1_q, (float*)grads->b1_q, (float*)grads->w2_q, (float*)grads->b2_q,
                     (float*)grads->w1_k, (float*)grads->b1_k, (float*)grads->w2_k, (float*)grads->b2_k};
     const int64_t gn[4] = {(int64_t)H * hid * d, (int64_t)H * hid, (int64_t)H * dp * hid, (int64_t)H * dp};
@@ -817,13 +821,17 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
   if (rc != REHYAT_OK) return rc;
   rc = launch_prefix_window(c, B, H, d, dp, nc, P.n_seg, P.nsplit, true);
   if (rc != REHYAT_OK) return rc;
-  rehyat_debug_out dbg;
-  dbg.m = dbg.aS = dbg.aL = nullptr;
-  dbg.nS = (float*)(ws + P.nS);
-  dbg.nL = (float*)(ws + P.nL);
-  rc = launch_attn_window(c, q, k, v, phi, y, &dbg, B, H, T, HW, d, chunk, overlap, 0, nc, qtiles,
-                          REHYAT_STAB_ROWMAX, false);
-  if (rc != REHYAT_OK) return rc;
+  const float* nS = saved ? saved->nS : (const float*)(ws + P.nS);
+  const float* nL = saved ? saved->nL : (const float*)(ws + P.nL);
+  if (!saved) {
+    rehyat_debug_out dbg;
+    dbg.m = dbg.aS = dbg.aL = nullptr;
+    dbg.nS = (float*)(ws + P.nS);
+    dbg.nL = (float*)(ws + P.nL);
+    rc = launch_attn_window(c, q, k, v, phi, y, &dbg, B, H, T, HW, d, chunk, overlap, 0, nc, qtiles,
+                            REHYAT_STAB_ROWMAX, false);
+    if (rc != REHYAT_OK) return rc;
+  }
 
   hipError_t e;
   TransposeArgs tr;   // W2 [dp][hidden] -> [hidden][dp] of both maps
@@ -841,8 +849,8 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
   PrepArgs pa;
   pa.g = (const bf16_t*)grad_out;
   pa.y = (const bf16_t*)y;
-  pa.nS = (const float*)(ws + P.nS);
-  pa.nL = (const float*)(ws + P.nL);
+  pa.nS = nS;
+  pa.nL = nL;
   pa.u = (bf16_t*)(ws + P.u);
   pa.tokw = (float*)(ws + P.tokw);
   pa.tokens = (int64_t)BH * N;

@@ -103,15 +103,21 @@ int main() {
     rehyat_phi_grads g;
     g.w1_q = g.b1_q = g.w2_q = g.b2_q = g.w1_k = g.b1_k = g.w2_k = g.b2_k = A;
     const size_t wb = rehyat_phi_backward_workspace_bytes(1, 12, 21, 1560, 128, 1);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, nullptr, A, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, nullptr, wb, nullptr) == REHYAT_E_NULL);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb - 1, nullptr) == REHYAT_E_WORKSPACE);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, (char*)A + 64, wb, nullptr) == REHYAT_E_WORKSPACE);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 2000, 1, 128, 1, 0, A, (size_t)1 << 40, nullptr) == REHYAT_E_UNSUPPORTED);
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, -1, A, wb, nullptr) == REHYAT_E_SHAPE);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, nullptr, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, nullptr, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, nullptr, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb - 1, nullptr) == REHYAT_E_WORKSPACE);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, (char*)A + 64, wb, nullptr) == REHYAT_E_WORKSPACE);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, &g, 1, 12, 2000, 1, 128, 1, 0, A, (size_t)1 << 40, nullptr) == REHYAT_E_UNSUPPORTED);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, &g, 1, 12, 21, 1560, 128, 1, -1, A, wb, nullptr) == REHYAT_E_SHAPE);
+    rehyat_forward_saved sv;
+    sv.nS = (const float*)A;
+    sv.nL = nullptr;
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, A, &sv, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+    sv.nL = (const float*)A;
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &sv, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
     g.b1_k = nullptr;
-    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
+    CHECK(rehyat_phi_backward(A, A, A, &phi, A, nullptr, nullptr, &g, 1, 12, 21, 1560, 128, 1, 0, A, wb, nullptr) == REHYAT_E_NULL);
   }
   CHECK(rehyat_profile_read(nullptr, nullptr) == REHYAT_E_NULL);
   for (int code = 1; code >= -7; --code) CHECK(std::strlen(rehyat_status_string(code)) > 0);

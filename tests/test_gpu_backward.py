@@ -185,3 +185,26 @@ def test_p320_chunk3_overlap1_gradients():
     """320x480 shape with the paper's preferred T_c = 3, T_o = 1 (section 4.1): key segments
     lag the chunks by one frame."""
     full_size_case("p320_t21_c3", 1, 4)
+
+
+def test_saved_forward_pass_gives_the_same_gradients():
+    """The distillation step has already run the forward pass: handing its output and the
+    components n^S, n^L to the gradient call skips the attention kernel there."""
+    B, H, T, HW, d, chunk, overlap = 1, 2, 5, 300, 128, 2, 1
+    q, k, v = synth.make_qkv(B, H, T * HW, d, seed=21)
+    phi = synth.make_phi(H, d, seed=22, gain=4.0)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    dG = synth.make_grad_out(B, H, T * HW, d, seed=23).to("cuda", torch.bfloat16)
+    g_full, y_full = binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, chunk, overlap=overlap)
+    out, comps = binding.forward(dq, dk, dv, dphi, T, HW, chunk, overlap=overlap, debug=True)
+    keep = out.clone()
+    g_saved, y_saved = binding.phi_backward(dq, dk, dv, dphi, dG, T, HW, chunk, overlap=overlap,
+                                            saved=(out, comps["nS"], comps["nL"]))
+    torch.cuda.synchronize()
+    assert torch.equal(y_saved, keep)            # the saved output is an input: untouched
+    # the two forward passes may split the chunk-state sums differently: equal up to that rounding
+    assert (y_full.float() - keep.float()).abs().max() <= 2.0 ** -7 * keep.float().abs().max()
+    for n in synth.PHI_NAMES:
+        a, b = g_full[n].double(), g_saved[n].double()
+        assert torch.isfinite(b).all(), n
+        assert (a - b).norm() <= 2e-3 * a.norm(), (n, float((a - b).norm() / a.norm()))

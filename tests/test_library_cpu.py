@@ -219,23 +219,27 @@ def test_phi_backward_validation_and_workspace_size():
     assert wsb(1, 2, 4, 8, 96, 1) == 0 and wsb(0, 2, 4, 8, 64, 1) == 0
     assert wsb(1, 2, 2000, 1, 64, 1) == 0                # more chunks than the entry point takes
     bw = lambda *a: lib.rehyat_phi_backward(*a)
-    #   q, k, v, phi, grad_out, out, grads, B, H, T, HW, d, chunk, overlap, ws, ws_bytes, stream
+    #   q, k, v, phi, grad_out, out, saved, grads, B, H, T, HW, d, chunk, overlap, ws, ws_bytes, stream
     base = (1, 2, 4, 8, 64, 1, 0)
-    assert bw(A, A, A, P(ok), None, A, P(g), *base, A, need, None) == binding.E_NULL
-    assert bw(A, A, A, P(ok), A, A, None, *base, A, need, None) == binding.E_NULL
-    assert bw(None, A, A, P(ok), A, A, P(g), *base, A, need, None) == binding.E_NULL
-    assert bw(A, A, A, P(ok), A, A, P(g), *base, None, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), None, A, None, P(g), *base, A, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), A, A, None, None, *base, A, need, None) == binding.E_NULL
+    assert bw(None, A, A, P(ok), A, A, None, P(g), *base, A, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), A, A, None, P(g), *base, None, need, None) == binding.E_NULL
     gn = binding.PhiGrads(*([A] * 8))
     gn.b2_k = None
-    assert bw(A, A, A, P(ok), A, A, P(gn), *base, A, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), A, A, None, P(gn), *base, A, need, None) == binding.E_NULL
     gm = binding.PhiGrads(*([A] * 8))
     gm.w1_q = A + 2
-    assert bw(A, A, A, P(ok), A, A, P(gm), *base, A, need, None) == binding.E_SHAPE
-    assert bw(A, A, A, P(ok), A + 8, A, P(g), *base, A, need, None) == binding.E_SHAPE      # grad_out misaligned
-    assert bw(A, A, A, P(ok), A, A, P(g), *base, A + 16, need, None) == binding.E_WORKSPACE
-    assert bw(A, A, A, P(ok), A, A, P(g), *base, A, need - 1, None) == binding.E_WORKSPACE
-    assert bw(A, A, A, P(ok), A, A, P(g), 1, 2, 4, 8, 64, 1, -1, A, need, None) == binding.E_SHAPE
-    assert bw(A, A, A, P(ok), A, A, P(g), 1, 2, 2000, 1, 64, 1, 0, A, 1 << 40, None) == binding.E_UNSUPPORTED
-    assert bw(A, A, A, P(ok), A, A, P(g), 1, 2, 4, 8, 32, 1, 0, A, need, None) == binding.E_UNSUPPORTED
+    assert bw(A, A, A, P(ok), A, A, None, P(gm), *base, A, need, None) == binding.E_SHAPE
+    assert bw(A, A, A, P(ok), A + 8, A, None, P(g), *base, A, need, None) == binding.E_SHAPE      # grad_out misaligned
+    assert bw(A, A, A, P(ok), A, A, None, P(g), *base, A + 16, need, None) == binding.E_WORKSPACE
+    assert bw(A, A, A, P(ok), A, A, None, P(g), *base, A, need - 1, None) == binding.E_WORKSPACE
+    assert bw(A, A, A, P(ok), A, A, None, P(g), 1, 2, 4, 8, 64, 1, -1, A, need, None) == binding.E_SHAPE
+    assert bw(A, A, A, P(ok), A, A, None, P(g), 1, 2, 2000, 1, 64, 1, 0, A, 1 << 40, None) == binding.E_UNSUPPORTED
+    assert bw(A, A, A, P(ok), A, A, None, P(g), 1, 2, 4, 8, 32, 1, 0, A, need, None) == binding.E_UNSUPPORTED
+    sv = binding.ForwardSaved(A, A)
+    assert bw(A, A, A, P(ok), A, None, P(sv), P(g), *base, A, need, None) == binding.E_NULL   # saved needs out
+    assert bw(A, A, A, P(ok), A, A, P(binding.ForwardSaved(A, None)), P(g), *base, A, need, None) == binding.E_NULL
+    assert bw(A, A, A, P(ok), A, A, P(binding.ForwardSaved(A + 2, A)), P(g), *base, A, need, None) == binding.E_SHAPE
     # N at or beyond 2^31 / (4 d): tile offsets of the token-major buffers would not fit 32 bits
-    assert bw(A, A, A, P(ok), A, A, P(g), 1, 1, 1 << 12, 1 << 11, 64, 1 << 12, 0, A, 1 << 40, None) == binding.E_SHAPE
+    assert bw(A, A, A, P(ok), A, A, None, P(g), 1, 1, 1 << 12, 1 << 11, 64, 1 << 12, 0, A, 1 << 40, None) == binding.E_SHAPE
