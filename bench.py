@@ -30,8 +30,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # and valid for the library version they were measured on (profiles/*_hbm_traffic_pmc.md).
 # Anything else reports null.
 ATTN_TRAFFIC = {
-    # 2.0 x 172,452 KiB + 1.0 x 98,280 KiB (profiles/wan480p_hbm_traffic_pmc.md)
-    ("wan480p", "forward", 301): 453_800_000,
+    # 2.0 x 178,195 KiB + 1.0 x 98,281 KiB (profiles/wan480p_hbm_traffic_pmc.md)
+    ("wan480p", "forward", 302): 465_600_000,
 }
 
 

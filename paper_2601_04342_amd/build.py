@@ -19,6 +19,13 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Wno-unused-command-line-argument"]
 
 
+# per-file additions: the attention kernel is about 1 % faster when the compiler's scheduler
+# favours instruction-level parallelism over register economy (213 instead of 238 registers
+# and no spills either way); the same strategy makes the chunk-state kernel 4 % slower and the
+# gradient kernels spill, so they keep the default
+EXTRA_FLAGS = {"rehyat_attn.hip": ["-mllvm", "-amdgpu-sched-strategy=max-ilp"]}
+
+
 def build_library(force=True, verbose=False):
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
     deps = srcs + [os.path.join(CSRC, h) for h in HEADERS] + [
@@ -31,7 +38,7 @@ def build_library(force=True, verbose=False):
     for s in srcs:
         o = os.path.join(CSRC, os.path.basename(s).replace(".hip", ".o"))
         objs.append(o)
-        cmd = [HIPCC] + FLAGS + ["-c", s, "-o", o]
+        cmd = [HIPCC] + FLAGS + EXTRA_FLAGS.get(os.path.basename(s), []) + ["-c", s, "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

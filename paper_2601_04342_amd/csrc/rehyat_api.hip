@@ -609,7 +609,7 @@ Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
 
 extern "C" {
 
-int rehyat_version(void) { return 301; }
+int rehyat_version(void) { return 302; }
 
 const char* rehyat_status_string(int code) {
   switch (code) {
