@@ -30,8 +30,8 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # and valid for the library version they were measured on (profiles/*_hbm_traffic_pmc.md).
 # Anything else reports null.
 ATTN_TRAFFIC = {
-    # 2.0 x 178,195 KiB + 1.0 x 98,281 KiB (profiles/wan480p_hbm_traffic_pmc.md)
-    ("wan480p", "forward", 302): 465_600_000,
+    # 2.0 x 178,013 KiB + 1.0 x 98,280 KiB (profiles/wan480p_hbm_traffic_pmc.md)
+    ("wan480p", "forward", 303): 465_200_000,
 }
 
 
@@ -144,6 +144,10 @@ def main():
                     help="after the timed steps also run one plain device-to-device copy of this "
                          "many MiB (a kernel of known HBM traffic that calibrates the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--xcd-mask", type=lambda x: int(x, 0), default=0xFF,
+                    help="measurement hook, timing only (forward modes): attention workgroups on the "
+                         "XCDs whose bit is clear exit at once, the others do their usual share; the "
+                         "output is then incomplete and is not checked")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (no sharding, no collectives); "
@@ -156,6 +160,12 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     binding.library()   # fails loudly if the HIP library is not built
+    probe = (args.xcd_mask & 0xFF) != 0xFF
+    if probe:
+        if args.mode not in ("forward", "fullsoftmax", "bidirectional"):
+            print("bench.py: --xcd-mask applies to the whole-sequence forward modes", file=sys.stderr)
+            sys.exit(2)
+        binding.debug_set_xcd_mask(args.xcd_mask)
     w = synth.WORKLOADS[args.workload]
     chunk = w.T if args.mode == "fullsoftmax" else w.chunk
     q, k, v, phi = synth.make_workload(w)
@@ -225,7 +235,7 @@ def main():
 
     if args.mode == "stream":
         out = torch.cat([p[3] for p in pieces], dim=2)
-    assert torch.isfinite(out.float()).all()
+    assert probe or torch.isfinite(out.float()).all()
     copy_gbps = None
     if args.pmc_copy_mib > 0:
         src = torch.full((args.pmc_copy_mib << 20,), 7, dtype=torch.uint8, device="cuda")
@@ -318,7 +328,10 @@ def main():
         "state_kernel_tflops": (fl["state_kernel"] / (prof["state"][0] / args.steps * 1e-3) / 1e12
                                 if prof["state"][1] else None),
     }
-    if not args.no_cpu_baseline and args.mode == "forward":
+    if probe:
+        res["probe"] = (f"xcd_mask={args.xcd_mask & 0xFF:#04x}: attention workgroups on the other XCDs exit at once; "
+                        "timing only, `value`, `tflops` and `roofline` do not describe a complete call")
+    if not args.no_cpu_baseline and args.mode == "forward" and not probe:
         res["cpu_baseline"], res["parity"] = cpu_baseline(w, chunk, q, k, v, phi, args.cpu_heads, out)
     print(json.dumps(res))
 

@@ -318,6 +318,18 @@ int rehyat_state(const void *k, const void *v,
 int rehyat_profile_enable(int on);
 int rehyat_profile_read(double *total_ms, int *launches);
 
+/*
+ * Measurement hook, timing only.  The hardware deals the workgroups of a launch
+ * round-robin to the chip's eight XCDs (workgroup index modulo 8).  With bit x of
+ * `mask` clear, the attention kernel's workgroups on XCD x exit at once and
+ * their rows of `out` are NOT written; the other XCDs do exactly their usual
+ * share.  Timing such launches against full ones shows how much the work of one
+ * XCD is slowed by activity on the others.  The mask is process-wide and stays
+ * until changed; 0xFF (the default) is normal operation.  Bits above the low
+ * eight are ignored; a mask with no low bit set is REHYAT_E_SHAPE.
+ */
+int rehyat_debug_set_xcd_mask(unsigned mask);
+
 /* Free library-owned device memory.  Safe to call more than once. */
 int rehyat_shutdown(void);
 

@@ -24,7 +24,7 @@ EXPORTS = ("rehyat_chunk_plan", "rehyat_workspace_bytes", "rehyat_set_workspace"
            "rehyat_phi_backward", "rehyat_phi_backward_workspace_bytes",
            "rehyat_status_string", "rehyat_version", "rehyat_last_hip_error",
            "rehyat_attn_kernel_name",
-           "rehyat_profile_enable", "rehyat_profile_read")
+           "rehyat_profile_enable", "rehyat_profile_read", "rehyat_debug_set_xcd_mask")
 
 
 class PhiParams(ctypes.Structure):
@@ -117,6 +117,8 @@ def _load():
     lib.rehyat_attn_kernel_name.argtypes = [ci]
     lib.rehyat_profile_enable.restype = ci
     lib.rehyat_profile_enable.argtypes = [ci]
+    lib.rehyat_debug_set_xcd_mask.restype = ci
+    lib.rehyat_debug_set_xcd_mask.argtypes = [ctypes.c_uint]
     lib.rehyat_profile_read.restype = ci
     lib.rehyat_profile_read.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ci)]
     _lib = lib
@@ -184,6 +186,13 @@ def profile_enable(on=True):
     rc = _load().rehyat_profile_enable(1 if on else 0)
     if rc != OK:
         raise RehyatError(rc, "rehyat_profile_enable")
+
+
+def debug_set_xcd_mask(mask):
+    """Measurement hook (timing only): attention workgroups on XCDs whose bit is clear exit at once."""
+    rc = _load().rehyat_debug_set_xcd_mask(int(mask))
+    if rc != OK:
+        raise RehyatError(rc, "rehyat_debug_set_xcd_mask")
 
 
 def profile_read():

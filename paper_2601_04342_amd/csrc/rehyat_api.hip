@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 
 #include "../../include/rehyat.h"
@@ -41,6 +42,7 @@ struct Workspace {
 Workspace g_ws;
 std::mutex g_mu;
 char g_hip_err[256] = "";
+std::atomic<unsigned> g_xcd_mask{0xFFu};   // rehyat_debug_set_xcd_mask
 
 int hip_fail(hipError_t e, const char* what) {
   snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
@@ -277,6 +279,7 @@ int launch_attn_window(const Ctx& c, const void* q, const void* k, const void* v
   a.q_bh_stride = a.kv_bh_stride = (int64_t)T * HW * d;
   a.step_nq = a.step_nwin = 0;
   a.all_linear = bidir ? 1 : 0;
+  a.xcd_mask = g_xcd_mask.load();
   hipError_t e;
   {
     ProfScope prof(c.prof, 2, c.st);
@@ -609,7 +612,7 @@ Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
 
 extern "C" {
 
-int rehyat_version(void) { return 302; }
+int rehyat_version(void) { return 303; }
 
 const char* rehyat_status_string(int code) {
   switch (code) {
@@ -923,6 +926,12 @@ int rehyat_phi_backward(const void* q, const void* k, const void* v, const rehya
                        HW, d, chunk, overlap, 0, cl.s_lo);
 }
 
+int rehyat_debug_set_xcd_mask(unsigned mask) {
+  if ((mask & 0xFFu) == 0) return REHYAT_E_SHAPE;
+  g_xcd_mask.store(mask & 0xFFu);
+  return REHYAT_OK;
+}
+
 int rehyat_profile_enable(int on) {
   std::lock_guard<std::mutex> lock(g_mu);
   g_prof.on = on != 0;
@@ -1070,6 +1079,7 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   a.step_nq = n_q;
   a.step_nwin = n_win;
   a.all_linear = 0;
+  a.xcd_mask = 0xFFu;   // the measurement hook covers whole-sequence calls only
   a.n_short = 0;
   {
     ProfScope prof(true, 2, st);

@@ -318,6 +318,7 @@ attn_kernel(AttnArgs a) {
   const int r = lane & 31;
 
   // ---- which work item -------------------------------------------------
+  if (!((a.xcd_mask >> (blockIdx.x & 7)) & 1u)) return;   // measurement hook; all bits set normally
   int qt, tc, bh;
   if (a.n_short == 0) {
     const int item = xcd_swizzle(blockIdx.x, a.items_per_xcd);

@@ -77,6 +77,7 @@ struct AttnArgs {
                            // the softmax window is rows [0, step_nwin) of k / v, the linear
                            // state is slot 0; the frame geometry above is then unused
   int all_linear;          // 1: every chunk reads a state (bidirectional sets of Eq. 11-12)
+  unsigned xcd_mask;       // measurement hook: workgroups on XCD x (index % 8) run only if bit x is set
 };
 
 // ---- transposes the carry into the [dprime][d] layout of the public state hook ----
