@@ -225,3 +225,29 @@ def test_state_hook_before_the_first_frame_is_zero():
     S, z = binding.state(dk, dv, dphi, T, HW, 0)
     torch.cuda.synchronize()
     assert (S == 0).all() and (z == 0).all()
+
+
+def test_xcd_mask_hook_skips_whole_workgroups_and_resets():
+    """The measurement hook: with some XCDs masked, every output row is either untouched or
+    bit-identical to the unmasked result (whole workgroups exit, nothing else changes), and
+    the full mask restores normal operation."""
+    B, H, T, HW, d = 1, 3, 5, 300, 128
+    q, k, v = synth.make_qkv(B, H, T * HW, d, seed=71)
+    phi = synth.make_phi(H, d, seed=72, gain=3.0)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    want = binding.forward(dq, dk, dv, dphi, T, HW, 1)
+    torch.cuda.synchronize()
+    out = torch.full_like(want, float("nan"))
+    try:
+        binding.debug_set_xcd_mask(0x05)
+        binding.forward(dq, dk, dv, dphi, T, HW, 1, out=out)
+        torch.cuda.synchronize()
+    finally:
+        binding.debug_set_xcd_mask(0xFF)
+    written = ~torch.isnan(out.float()).any(dim=-1)
+    assert 0 < int(written.sum()) < written.numel()
+    assert torch.equal(out[written], want[written])
+    assert torch.isnan(out[~written].float()).all()
+    again = binding.forward(dq, dk, dv, dphi, T, HW, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(again, want)

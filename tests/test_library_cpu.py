@@ -243,3 +243,13 @@ def test_phi_backward_validation_and_workspace_size():
     assert bw(A, A, A, P(ok), A, A, P(binding.ForwardSaved(A + 2, A)), P(g), *base, A, need, None) == binding.E_SHAPE
     # N at or beyond 2^31 / (4 d): tile offsets of the token-major buffers would not fit 32 bits
     assert bw(A, A, A, P(ok), A, A, None, P(g), 1, 1, 1 << 12, 1 << 11, 64, 1 << 12, 0, A, 1 << 40, None) == binding.E_SHAPE
+
+
+def test_xcd_mask_hook_validation():
+    """The measurement hook takes any mask with a low bit set and refuses one with none;
+    setting it launches nothing."""
+    lib = binding.library()
+    assert lib.rehyat_debug_set_xcd_mask(0) == binding.E_SHAPE
+    assert lib.rehyat_debug_set_xcd_mask(0x100) == binding.E_SHAPE
+    assert lib.rehyat_debug_set_xcd_mask(0x01) == binding.OK
+    assert lib.rehyat_debug_set_xcd_mask(0xFF) == binding.OK
