@@ -144,6 +144,10 @@ def main():
                     help="after the timed steps also run one plain device-to-device copy of this "
                          "many MiB (a kernel of known HBM traffic that calibrates the FETCH_SIZE / "
                          "WRITE_SIZE counters of a rocprofv3 --pmc run)")
+    ap.add_argument("--graph-steps", type=int, default=0,
+                    help="forward modes: also record this many consecutive calls into one HIP graph and "
+                         "report the time of a step when the graph is replayed (`ms_per_step_graph_replay`); "
+                         "`value` stays the eager figure")
     ap.add_argument("--xcd-mask", type=lambda x: int(x, 0), default=0xFF,
                     help="measurement hook, timing only (forward modes): attention workgroups on the "
                          "XCDs whose bit is clear exit at once, the others do their usual share; the "
@@ -232,6 +236,30 @@ def main():
     torch.cuda.synchronize()
     prof = binding.profile_read()
     binding.profile_enable(False)
+
+    graph_ms = None
+    if args.graph_steps > 0 and args.mode in ("forward", "fullsoftmax", "bidirectional"):
+        # the workspace is in place after the passes above: a call only enqueues kernels
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            for _ in range(args.graph_steps):
+                step()
+        n_rep = max(3, args.steps // args.graph_steps)
+        for _ in range(2):
+            graph.replay()
+        g = [torch.cuda.Event(enable_timing=True) for _ in range(n_rep + 1)]
+        torch.cuda.synchronize()
+        g[0].record()
+        for i in range(n_rep):
+            graph.replay()
+            g[i + 1].record()
+        torch.cuda.synchronize()
+        graph_ms = statistics.median(g[i].elapsed_time(g[i + 1]) for i in range(n_rep)) / args.graph_steps
 
     if args.mode == "stream":
         out = torch.cat([p[3] for p in pieces], dim=2)
@@ -328,6 +356,9 @@ def main():
         "state_kernel_tflops": (fl["state_kernel"] / (prof["state"][0] / args.steps * 1e-3) / 1e12
                                 if prof["state"][1] else None),
     }
+    if graph_ms is not None:
+        res["ms_per_step_graph_replay"] = graph_ms
+        res["graph_steps"] = args.graph_steps
     if probe:
         res["probe"] = (f"xcd_mask={args.xcd_mask & 0xFF:#04x}: attention workgroups on the other XCDs exit at once; "
                         "timing only, `value`, `tflops` and `roofline` do not describe a complete call")
