@@ -14,11 +14,13 @@ from tests import parity
 pytestmark = pytest.mark.gpu
 
 
-def stream(dq, dk, dv, dphi, T, HW, chunk, overlap, stab=0, absorb_all_at_end=False, on_step=None):
-    """Drive rehyat_step over the chunks of a sequence; returns (out, S, z)."""
+def stream(dq, dk, dv, dphi, T, HW, chunk, overlap, stab=0, absorb_all_at_end=False, on_step=None,
+           state_offset=0):
+    """Drive rehyat_step over the chunks of a sequence; returns (out, S, z).  `state_offset`
+    floats are skipped in front of S, so that it is only 4-byte aligned."""
     B, H, N, d = dq.shape
     plan = binding.chunk_plan(T, HW, chunk, overlap).tolist()
-    S = torch.zeros(B, H, 2 * d, d, device="cuda")
+    S = torch.zeros(state_offset + B * H * 2 * d * d, device="cuda")[state_offset:].view(B, H, 2 * d, d)
     z = torch.zeros(B, H, 2 * d, device="cuda")
     out = torch.empty_like(dq)
     for t, (q_lo, q_hi, s_lo, s_hi, l_hi) in enumerate(plan):
@@ -108,3 +110,16 @@ def test_streaming_full_size_wan480p():
     full = binding.forward(dq, dk, dv, dphi, w.T, w.HW, w.chunk, overlap=1)
     torch.cuda.synchronize()
     assert (out.float() - full.float()).abs().max().item() <= parity.OUT_MAX_ABS
+
+
+def test_state_that_is_only_four_byte_aligned():
+    """The caller's state may sit at any 4-byte boundary: same bits as with an aligned one."""
+    B, H, T, HW, d = 1, 2, 5, 130, 128
+    q, k, v = synth.make_qkv(B, H, T * HW, d, seed=33)
+    phi = synth.make_phi(H, d, seed=34, gain=3.0)
+    dq, dk, dv, dphi = parity.to_device(q, k, v, phi)
+    a = stream(dq, dk, dv, dphi, T, HW, 1, 1)
+    b = stream(dq, dk, dv, dphi, T, HW, 1, 1, state_offset=1)
+    assert b[1].data_ptr() % 16 == 4
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
