@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 # Anything else reports null.
 ATTN_TRAFFIC = {
     # 2.0 x 178,013 KiB + 1.0 x 98,280 KiB (profiles/wan480p_hbm_traffic_pmc.md)
-    ("wan480p", "forward", 303): 465_200_000,
+    ("wan480p", "forward", 304): 465_200_000,   # 303 and 304 share the forward kernels
 }
 
 

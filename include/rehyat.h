@@ -286,6 +286,15 @@ int rehyat_phi_backward(const void *q, const void *k, const void *v,
  * s_lo(t+1) - s_lo(t) of rehyat_chunk_plan, gives the outputs of
  * rehyat_forward_ex (same overlap) up to the rounding of a different summation
  * split.  Asynchronous on `stream`; uses the workspace like a forward call.
+ * The state update (the pieces of Eq. 17-18 and their addition to S and z) does
+ * not feed this chunk's output, so it runs beside the attention kernel on a
+ * second stream that the library creates per device on first use (default
+ * priority, kept until the process ends), forked from `stream` after the state
+ * has been copied for the read-out and joined to it before the call's work on
+ * `stream` is complete: to the caller the call is ordered on `stream` like any
+ * other, also under stream capture (fork and join become graph edges).  When
+ * the first call on a device happens while `stream` is being captured, nothing
+ * is created and the update runs on `stream` itself.
  * Supported: d in {64, 128}.
  */
 int rehyat_step(const void *q_t, const void *k_win, const void *v_win,

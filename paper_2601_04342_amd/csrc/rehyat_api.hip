@@ -44,6 +44,15 @@ std::mutex g_mu;
 char g_hip_err[256] = "";
 std::atomic<unsigned> g_xcd_mask{0xFFu};   // rehyat_debug_set_xcd_mask
 
+// rehyat_step runs the state update of a chunk beside its attention kernel: a second stream
+// per device, forked from and joined to the caller's stream with two events (all at the
+// default priority; created on first use, kept until the process ends).
+struct SideStream {
+  hipStream_t s = nullptr;
+  hipEvent_t fork = nullptr, join = nullptr;
+};
+SideStream g_side[64];
+
 int hip_fail(hipError_t e, const char* what) {
   snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
   return REHYAT_E_HIP;
@@ -112,6 +121,30 @@ struct Ctx {
   hipStream_t st;
   bool prof;  // record per-kernel events (library-held workspace only)
 };
+
+// The side stream of the current device, or nullptr when there is none and none can be made
+// now (the caller's stream is being captured: nothing is created inside a capture).
+SideStream* side_stream(hipStream_t main) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  SideStream& ss = g_side[dev];
+  if (ss.s) return &ss;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(main, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return nullptr;
+  hipStream_t st = nullptr;
+  hipEvent_t a = nullptr, b = nullptr;
+  if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return nullptr;
+  if (hipEventCreateWithFlags(&a, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&b, hipEventDisableTiming) != hipSuccess) {
+    if (a) (void)hipEventDestroy(a);
+    (void)hipStreamDestroy(st);
+    return nullptr;
+  }
+  ss.s = st;
+  ss.fork = a;
+  ss.join = b;
+  return &ss;
+}
 
 bool supported_dims(int d, int dp) { return (d == 64 || d == 128) && dp == 2 * d; }
 
@@ -612,7 +645,7 @@ Slots slots_that_fit(int B, int H, int d, int dp, size_t bytes) {
 
 extern "C" {
 
-int rehyat_version(void) { return 303; }
+int rehyat_version(void) { return 304; }
 
 const char* rehyat_status_string(int code) {
   switch (code) {
@@ -998,14 +1031,40 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
   const WsLayout& L = c.L;
 
   hipError_t e;
-  // increment of the tokens that leave the window, in pieces
+  StepStateArgs ss;
+  ss.S = S;
+  ss.z = z;
+  ss.partial = (const float*)(ws + L.partial);
+  ss.state_s = (bf16_t*)(ws + L.state_s);
+  ss.state_z = (float*)(ws + L.state_z);
+  ss.BH = B * H;
+  ss.d = d;
+  ss.dprime = dp;
+  ss.partial_slots = c.sl.partial;
+  ss.state_slots = c.sl.state;
+  // The read-out of this chunk uses the caller's state as it is (Eq. 16): slot 0 <- S, z.  The
+  // tokens that leave the window are absorbed afterwards (Eq. 17-18: state kernel in pieces,
+  // then S, z += the pieces, in place and in the caller's layout); the attention kernel does
+  // not depend on that and runs beside it when a second stream is at hand.
+  SideStream* side = n_absorb > 0 ? side_stream(st) : nullptr;
+  hipStream_t upd = side ? side->s : st;   // stream of the state update
   int nsplit = 1;
   if (n_absorb > 0) {
-    // one segment only: enough pieces to cover the chip, none shorter than a tile
-    nsplit = (2 * kCUs + B * H - 1) / (B * H);
+    // One segment only, cut into pieces: one workgroup of the state kernel fills a CU, and a
+    // piece pays the workgroup's set-up (its weight slices into registers) once.  Beside the
+    // attention kernel, which spreads its workgroups over as many CUs, the pieces should fit
+    // the CUs it leaves free; alone, three quarters of the chip measured best (480p shape,
+    // 12 heads: 8 pieces forked, 16 serial; 25 pieces of one tile each were 30 % slower).
+    const int attn_wgs = B * H * ((n_q + attn_query_tile(d) - 1) / attn_query_tile(d));
+    int free_cus = side ? kCUs - attn_wgs : 3 * kCUs / 4;
+    if (free_cus < kCUs / 4) free_cus = kCUs / 4;
+    nsplit = free_cus / (B * H);
+    if (nsplit < 1) nsplit = 1;
     if (nsplit > c.sl.partial) nsplit = c.sl.partial;
     const int max_pieces = (n_absorb + 63) / 64;
     if (nsplit > max_pieces) nsplit = max_pieces;
+  }
+  auto launch_absorb_pieces = [&]() -> int {
     StateArgs s;
     s.k = (const bf16_t*)k_win;
     s.v = (const bf16_t*)v_win;
@@ -1026,25 +1085,42 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
     s.kv_bh_stride = (int64_t)n_win * d;
     s.step_n = n_absorb;
     s.query_segments = 0;
-    ProfScope prof(true, 0, st);
-    e = launch_state(s, d, s.items_per_xcd * 8, st);
-    if (e != hipSuccess) return hip_fail(e, "state kernel launch");
-  }
-  // slot 0 <- the caller's state as it is (what the read-out of this chunk uses, Eq. 16); then
-  // the caller's state += the pieces (Eq. 17-18), in place and in its own layout
-  {
-    StepStateArgs ss;
-    ss.S = S;
-    ss.z = z;
-    ss.partial = (const float*)(ws + L.partial);
-    ss.state_s = (bf16_t*)(ws + L.state_s);
-    ss.state_z = (float*)(ws + L.state_z);
-    ss.BH = B * H;
-    ss.d = d;
-    ss.dprime = dp;
+    ProfScope prof(true, 0, upd);
+    hipError_t es = launch_state(s, d, s.items_per_xcd * 8, upd);
+    if (es != hipSuccess) return hip_fail(es, "state kernel launch");
+    return REHYAT_OK;
+  };
+  if (side) {
+    // caller's stream: slot 0 <- state; fork; second stream: pieces, then state += pieces
+    ss.nsplit = 0;
+    ss.write_slot = 1;
+    {
+      ProfScope prof(true, 1, st);
+      e = launch_step_state(ss, st);
+    }
+    if (e != hipSuccess) return hip_fail(e, "step state kernel launch");
+    e = hipEventRecord(side->fork, st);
+    if (e == hipSuccess) e = hipStreamWaitEvent(side->s, side->fork, 0);
+    if (e != hipSuccess) return hip_fail(e, "fork to the second stream");
+    rc = launch_absorb_pieces();
+    if (rc != REHYAT_OK) return rc;
+    ss.nsplit = nsplit;
+    ss.write_slot = 0;
+    {
+      ProfScope prof(true, 1, upd);
+      e = launch_step_state(ss, upd);
+    }
+    if (e != hipSuccess) return hip_fail(e, "step state kernel launch");
+    e = hipEventRecord(side->join, side->s);
+    if (e != hipSuccess) return hip_fail(e, "hipEventRecord(join)");
+  } else {
+    // one stream: pieces, then slot 0 <- state and state += pieces in one kernel
+    if (n_absorb > 0) {
+      rc = launch_absorb_pieces();
+      if (rc != REHYAT_OK) return rc;
+    }
     ss.nsplit = n_absorb > 0 ? nsplit : 0;
-    ss.partial_slots = c.sl.partial;
-    ss.state_slots = c.sl.state;
+    ss.write_slot = 1;
     ProfScope prof(true, 1, st);
     e = launch_step_state(ss, st);
     if (e != hipSuccess) return hip_fail(e, "step state kernel launch");
@@ -1086,7 +1162,10 @@ int rehyat_step(const void* q_t, const void* k_win, const void* v_win, const reh
     e = launch_attn(a, d, a.items_per_xcd * 8, st);
   }
   if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
-
+  if (side) {   // the call's work is complete, for the caller's stream, when both branches are
+    e = hipStreamWaitEvent(st, side->join, 0);
+    if (e != hipSuccess) return hip_fail(e, "join of the second stream");
+  }
   return REHYAT_OK;
 }
 

@@ -117,6 +117,7 @@ struct StepStateArgs {
   int BH, d, dprime;
   int nsplit;            // pieces to add (0: the state is only copied into slot 0)
   int partial_slots, state_slots;
+  int write_slot;        // 1: slot 0 <- the state as it is before the pieces are added
 };
 
 // =================================================================================

@@ -112,27 +112,31 @@ step_state_kernel(StepStateArgs a) {
     const int f4 = tid & 15, el = tid >> 4;   // features 4 f4 .. 4 f4 + 3 of row e0 + el of S^T
     const int64_t o = (int64_t)(e0 + el) * a.dprime + f0 + 4 * f4;
     f32x4 v = {tile[4 * f4][el], tile[4 * f4 + 1][el], tile[4 * f4 + 2][el], tile[4 * f4 + 3][el]};
-    u32x2 pk;
-    pk[0] = pack_bf16(v[0], v[1]);
-    pk[1] = pack_bf16(v[2], v[3]);
-    *reinterpret_cast<u32x2*>(slot + o) = pk;
+    if (a.write_slot) {
+      u32x2 pk;
+      pk[0] = pack_bf16(v[0], v[1]);
+      pk[1] = pack_bf16(v[2], v[3]);
+      *reinterpret_cast<u32x2*>(slot + o) = pk;
+    }
 #pragma unroll 8
     for (int sp = 0; sp < a.nsplit; ++sp) v += *reinterpret_cast<const f32x4*>(part + (int64_t)sp * elems + o);
 #pragma unroll
     for (int i = 0; i < 4; ++i) tile[4 * f4 + i][el] = v[i];
   }
   __syncthreads();
+  if (a.nsplit > 0) {   // nothing added: the caller's state stays as it is
 #pragma unroll
-  for (int m = 0; m < 4; ++m) {
-    const int idx = tid + 256 * m, row = idx >> 4, col = idx & 15;
-    S[(int64_t)(f0 + row) * a.d + e0 + col] = tile[row][col];
+    for (int m = 0; m < 4; ++m) {
+      const int idx = tid + 256 * m, row = idx >> 4, col = idx & 15;
+      S[(int64_t)(f0 + row) * a.d + e0 + col] = tile[row][col];
+    }
   }
   if (blockIdx.y == 0 && tid < 64) {   // z of this block's 64 features
     const int f = f0 + tid;
     float v = a.z[(int64_t)bh * a.dprime + f];
-    a.state_z[(int64_t)bh * a.state_slots * a.dprime + f] = v;
+    if (a.write_slot) a.state_z[(int64_t)bh * a.state_slots * a.dprime + f] = v;
     for (int sp = 0; sp < a.nsplit; ++sp) v += part[(int64_t)sp * elems + n + f];
-    a.z[(int64_t)bh * a.dprime + f] = v;
+    if (a.nsplit > 0) a.z[(int64_t)bh * a.dprime + f] = v;
   }
 }
 
