@@ -51,7 +51,7 @@ struct SideStream {
   hipStream_t s = nullptr;
   hipEvent_t fork = nullptr, join = nullptr;
 };
-SideStream g_side[64];
+SideStream g_side[kMaxDevices];
 
 int hip_fail(hipError_t e, const char* what) {
   snprintf(g_hip_err, sizeof(g_hip_err), "%s: %s", what, hipGetErrorString(e));
@@ -126,7 +126,7 @@ struct Ctx {
 // now (the caller's stream is being captured: nothing is created inside a capture).
 SideStream* side_stream(hipStream_t main) {
   int dev = -1;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
   SideStream& ss = g_side[dev];
   if (ss.s) return &ss;
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
